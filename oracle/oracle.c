@@ -1,0 +1,186 @@
+/*
+ * CPU oracle for the fused operator chain
+ *
+ *     Y = LayerNorm_N( GELU( X * W^T + b ) ) * gamma + beta
+ *
+ * THIS IS TEST INFRASTRUCTURE, NOT PRODUCT CODE.  It is a plain, slow, fp64
+ * evaluation of the operator's definition, written to be checked by eye.  It
+ * shares no source, header, table or helper with the GPU library; only tests,
+ * the smoke check and the benchmark's CPU-baseline leg may call it.
+ *
+ * What it follows.  The paper frames every task as "be functionally
+ * equivalent to the PyTorch reference operator on the same inputs, within a
+ * small tolerance" (Sec. 2.1 problem statement; Sec. 2.2 "Design of
+ * Correctness Tests").  It prints no formula for this chain, so the oracle is
+ * the public definition of the three operators written out:
+ *   linear     z[m][n] = b[n] + sum_k X[m][k] * W[n][k]          (W is [N,K])
+ *   GELU       g = z * Phi(z),  Phi(z) = 0.5 * erfc(-z / sqrt 2)   (erf form)
+ *   LayerNorm  mu = mean_n g,  var = mean_n (g - mu)^2  (biased),
+ *              y = (g - mu) / sqrt(var + eps) * gamma[n] + beta[n]
+ * The row reduction is the quantity the paper's fused-epilogue case study
+ * (App. B.1) and its row-reduction case study (Sec. 4) revolve around.
+ *
+ * Inputs are the exact values handed to the GPU, widened to fp64 (bf16 -> fp32
+ * -> fp64 is exact).  Every sum runs in index order; rows are independent and
+ * are distributed over host threads with OpenMP, nothing else is parallel.
+ *
+ * Parity pins (tests/test_oracle_pins.py): GELU against a 50-digit series for
+ * erf; GELU(z) - GELU(-z) = z; LayerNorm mean/variance closed forms; scale and
+ * shift behaviour of LayerNorm; constant rows; hand-expanded tiny GEMMs with
+ * non-square shapes; integer-valued exact GEMMs; X = I; an independent
+ * float64 library composition.  No function here is unpinned.
+ *
+ * Build: gcc -O2 -fno-fast-math -ffp-contract=off -fopenmp -shared -fPIC
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stddef.h>
+#include <stdlib.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+/* Number of host threads the row loop will use. */
+int oracle_num_threads(void)
+{
+#ifdef _OPENMP
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}
+
+/* GELU, erf form:  g = z * Phi(z) = 0.5 * z * erfc(-z / sqrt(2)).
+ * erfc keeps full relative accuracy for z << 0, where 1 + erf cancels. */
+double oracle_gelu(double z)
+{
+    return 0.5 * z * erfc(-z / sqrt(2.0));
+}
+
+/* z[n] = b[n] + sum_{k=0}^{K-1} x[k] * W[n][k], k ascending.  b may be NULL (0). */
+void oracle_linear_row(const float *x, const float *W, const float *b,
+                       int64_t K, int64_t N, double *z)
+{
+    for (int64_t n = 0; n < N; ++n) {
+        const float *w = W + (size_t)n * (size_t)K;
+        double acc = 0.0;
+        for (int64_t k = 0; k < K; ++k)
+            acc += (double)x[k] * (double)w[k];
+        z[n] = (b ? (double)b[n] : 0.0) + acc;
+    }
+}
+
+/* LayerNorm of one row of length N: two-pass mean and biased variance, eps
+ * inside the square root.  gamma / beta may be NULL (1 / 0).
+ * mu_out / var_out may be NULL. */
+void oracle_layernorm_row(const double *g, int64_t N, const float *gamma,
+                          const float *beta, double eps, double *y,
+                          double *mu_out, double *var_out)
+{
+    double s = 0.0;
+    for (int64_t n = 0; n < N; ++n)
+        s += g[n];
+    const double mu = s / (double)N;
+    double q = 0.0;
+    for (int64_t n = 0; n < N; ++n) {
+        const double d = g[n] - mu;
+        q += d * d;
+    }
+    const double var = q / (double)N;
+    const double denom = sqrt(var + eps);
+    for (int64_t n = 0; n < N; ++n) {
+        const double ga = gamma ? (double)gamma[n] : 1.0;
+        const double be = beta ? (double)beta[n] : 0.0;
+        y[n] = (g[n] - mu) / denom * ga + be;
+    }
+    if (mu_out)
+        *mu_out = mu;
+    if (var_out)
+        *var_out = var;
+}
+
+/*
+ * The whole chain for a set of rows.
+ *   X [M,K], W [N,K], b/gamma/beta [N] (each may be NULL), row-major fp32
+ *   holding the exact input values; eps as the fp32 the GPU receives.
+ *   rows: n_rows row indices into X, or NULL meaning rows 0..M-1 (n_rows
+ *   ignored, M rows are produced).
+ *   Y [R,N] fp64 out (R = number of rows produced).  Z, G [R,N] and mu, var [R]
+ *   are optional stage outputs (NULL to skip).
+ * Returns 0, or -1 on bad arguments / allocation failure.
+ */
+int oracle_fused_linear_gelu_ln(const float *X, const float *W, const float *b,
+                                const float *gamma, const float *beta, float eps,
+                                int64_t M, int64_t K, int64_t N,
+                                const int64_t *rows, int64_t n_rows,
+                                double *Y, double *Z, double *G,
+                                double *mu, double *var)
+{
+    if (!X || !W || !Y || M < 0 || K < 0 || N <= 0)
+        return -1;
+    const int64_t R = rows ? n_rows : M;
+    if (rows)
+        for (int64_t r = 0; r < R; ++r)
+            if (rows[r] < 0 || rows[r] >= M)
+                return -1;
+    const double eps64 = (double)eps;
+    int failed = 0;
+
+#pragma omp parallel
+    {
+        double *z = (double *)malloc((size_t)N * sizeof(double));
+        double *g = (double *)malloc((size_t)N * sizeof(double));
+        if (!z || !g) {
+#pragma omp atomic write
+            failed = 1;
+        }
+#pragma omp barrier
+        if (!failed) {
+#pragma omp for schedule(dynamic, 1)
+            for (int64_t r = 0; r < R; ++r) {
+                const int64_t m = rows ? rows[r] : r;
+                oracle_linear_row(X + (size_t)m * (size_t)K, W, b, K, N, z);
+                for (int64_t n = 0; n < N; ++n)
+                    g[n] = oracle_gelu(z[n]);
+                oracle_layernorm_row(g, N, gamma, beta, eps64,
+                                     Y + (size_t)r * (size_t)N,
+                                     mu ? mu + r : NULL, var ? var + r : NULL);
+                if (Z)
+                    for (int64_t n = 0; n < N; ++n)
+                        Z[(size_t)r * (size_t)N + n] = z[n];
+                if (G)
+                    for (int64_t n = 0; n < N; ++n)
+                        G[(size_t)r * (size_t)N + n] = g[n];
+            }
+        }
+        free(z);
+        free(g);
+    }
+    return failed ? -1 : 0;
+}
+
+/*
+ * Round fp64 values to the nearest bfloat16 value (8 significant bits,
+ * exponent range of fp32), ties to even, in one rounding step (not through
+ * fp32, which could round twice).  The result is returned as fp64.
+ * Subnormal bf16 values (quantum 2^-133) and overflow to infinity are handled.
+ */
+void oracle_round_bf16(const double *in, int64_t n, double *out)
+{
+    for (int64_t i = 0; i < n; ++i) {
+        const double x = in[i];
+        if (x == 0.0 || isnan(x) || isinf(x)) {
+            out[i] = x;
+            continue;
+        }
+        int e = ilogb(x);                 /* 2^e <= |x| < 2^(e+1) */
+        if (e < -126)
+            e = -126;                     /* subnormal range: fixed quantum */
+        const double q = ldexp(x, 7 - e); /* quantum becomes 1 */
+        const double r = nearbyint(q);    /* default mode: ties to even */
+        double y = ldexp(r, e - 7);
+        if (fabs(y) >= ldexp(1.0, 128))   /* beyond the largest finite bf16 */
+            y = x > 0 ? INFINITY : -INFINITY;
+        out[i] = y;
+    }
+}

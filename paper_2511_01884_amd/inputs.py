@@ -1,0 +1,103 @@
+"""Seeded synthetic inputs for the fused linear + GELU + LayerNorm operator.
+
+This module draws random tensors and nothing else: it holds none of the
+operator's arithmetic, so both the GPU library's tests and the CPU oracle's
+tests may use it.  The tensors stand in for the multi-step operator tasks the
+paper evaluates on (Sec. 3.1), whose task files are not reproduced here.
+
+Recipe (host generator, one stream per call, draw order X, W, b, gamma, beta,
+all drawn in float32, then rounded to nearest-even to the storage dtype; the
+rounded values are what every consumer sees):
+    X     ~ N(0, 1)                      [M, K]
+    W     ~ N(0, variance 1/K)           [N, K]   (so X W^T has unit variance)
+    b     ~ U(-0.1, 0.1)                 [N]
+    gamma = 1 + 0.1 * N(0, 1)            [N]      (all ones in the plain variant)
+    beta  = 0.1 * N(0, 1)                [N]      (all zeros in the plain variant)
+    eps   = 1e-5
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass
+from typing import Dict
+
+import torch
+
+EPS = 1e-5
+
+
+@dataclass(frozen=True)
+class Workload:
+    name: str
+    dtype: str  # "f32" or "bf16"
+    M: int
+    K: int
+    N: int
+    note: str
+
+
+# The five synthetic workloads the build is measured on.
+CONFIGS: Dict[str, Workload] = {
+    "cfg0": Workload("cfg0", "f32", 256, 512, 512, "fp32 parity case"),
+    "cfg1": Workload("cfg1", "bf16", 4096, 4096, 4096, "compute-bound square case"),
+    "cfg2": Workload("cfg2", "bf16", 65536, 1024, 1024, "tall-skinny, epilogue-heavy"),
+    "cfg3": Workload("cfg3", "bf16", 16, 8192, 8192, "small-M, streams W"),
+    "cfg4": Workload("cfg4", "bf16", 8192, 4096, 16384, "wide rows, many N tiles"),
+}
+
+
+def torch_dtype(dtype: str) -> torch.dtype:
+    if dtype == "f32":
+        return torch.float32
+    if dtype == "bf16":
+        return torch.bfloat16
+    raise ValueError("dtype must be 'f32' or 'bf16'")
+
+
+def make_inputs(M: int, K: int, N: int, dtype: str = "bf16", seed: int = 0,
+                plain_affine: bool = False) -> Dict[str, torch.Tensor]:
+    """CPU tensors X, W, b, gamma, beta in the storage dtype, plus eps."""
+    td = torch_dtype(dtype)
+    g = torch.Generator(device="cpu")
+    g.manual_seed(seed)
+    X = torch.randn(M, K, generator=g, dtype=torch.float32)
+    W = torch.randn(N, K, generator=g, dtype=torch.float32) * (float(K) ** -0.5)
+    b = torch.rand(N, generator=g, dtype=torch.float32) * 0.2 - 0.1
+    gamma = 1.0 + 0.1 * torch.randn(N, generator=g, dtype=torch.float32)
+    beta = 0.1 * torch.randn(N, generator=g, dtype=torch.float32)
+    if plain_affine:
+        gamma = torch.ones(N, dtype=torch.float32)
+        beta = torch.zeros(N, dtype=torch.float32)
+    return {
+        "X": X.to(td).contiguous(),
+        "W": W.to(td).contiguous(),
+        "b": b.to(td).contiguous(),
+        "gamma": gamma.to(td).contiguous(),
+        "beta": beta.to(td).contiguous(),
+        "eps": EPS,
+    }
+
+
+def make_integer_inputs(M: int, K: int, N: int, dtype: str = "bf16", seed: int = 0,
+                        lo: int = -4, hi: int = 4) -> Dict[str, torch.Tensor]:
+    """Integer-valued X, W, b in [lo, hi]: every product and partial sum of the
+    linear stage is an exactly representable integer for K * hi * hi < 2**24."""
+    td = torch_dtype(dtype)
+    g = torch.Generator(device="cpu")
+    g.manual_seed(seed)
+    X = torch.randint(lo, hi + 1, (M, K), generator=g).to(td)
+    W = torch.randint(lo, hi + 1, (N, K), generator=g).to(td)
+    b = torch.randint(lo, hi + 1, (N,), generator=g).to(td)
+    return {"X": X.contiguous(), "W": W.contiguous(), "b": b.contiguous()}
+
+
+def sample_rows(M: int, n: int, tile: int = 256, seed: int = 0):
+    """Row indices for sampled checks at full size: the rows next to tile
+    boundaries plus seeded random rows, sorted and unique."""
+    fixed = {0, M - 1}
+    for r in (tile - 1, tile, M - tile - 1, M - tile):
+        if 0 <= r < M:
+            fixed.add(r)
+    g = torch.Generator(device="cpu")
+    g.manual_seed(seed + 12345)
+    extra = torch.randint(0, M, (max(0, n - len(fixed)),), generator=g).tolist()
+    return sorted(fixed.union(extra))
