@@ -1,0 +1,176 @@
+#!/usr/bin/env python3
+"""Benchmark of the fused linear + erf-GELU + LayerNorm library on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg1]
+
+One step = one call of ff_fused_linear_gelu_ln (the whole hot path) on one
+synthetic batch already resident in HBM.  Successive steps rotate through
+distinct (X, W, Y) buffer sets whose total size exceeds the 256 MB Infinity
+Cache, so rates are HBM rates, not cache rates.  Prints ONE JSON line.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+# MI355X published peaks: 256 CUs x 4096 bf16 flop/clk x 2.4 GHz; HBM3E 8 TB/s.
+PEAK_BF16_TFLOPS = 2516.6
+PEAK_F32_TFLOPS = 157.3
+PEAK_HBM_GBS = 8000.0
+INFINITY_CACHE_BYTES = 256 << 20
+
+
+def algorithmic_bytes(M, K, N, esize):
+    """Each of X, W, b, gamma, beta read once and Y written once."""
+    return (M * K + N * K + M * N + 3 * N) * esize
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default="cfg1", help="cfg0..cfg4 (default: cfg1, the metric's workload)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-eager", action="store_true")
+    ap.add_argument("--cpu-seconds", type=float, default=12.0, help="target CPU time of the oracle sample")
+    args = ap.parse_args()
+
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on ONE GPU; the path shards by rows with no exchange "
+              "(see DESIGN.md), and no multi-GPU figure is produced. Re-run with --gpus 1.",
+              file=sys.stderr)
+        return 2
+
+    import torch
+    from paper_2511_01884_amd import binding as B
+    from paper_2511_01884_amd.inputs import CONFIGS, make_inputs
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 1
+    B.load()  # fails loudly if the HIP library is not built
+    torch.cuda.set_device(0)
+    wl = CONFIGS[args.workload]
+    M, K, N = wl.M, wl.K, wl.N
+    esize = 4 if wl.dtype == "f32" else 2
+    flops = 2.0 * M * K * N
+    abytes = algorithmic_bytes(M, K, N, esize)
+
+    d = make_inputs(M, K, N, wl.dtype, seed=0)
+    set_bytes = (M * K + N * K + M * N) * esize
+    n_sets = max(2, -(-int(1.5 * INFINITY_CACHE_BYTES) // set_bytes))
+    n_sets = min(n_sets, 16)
+    b, gamma, beta = d["b"].cuda(), d["gamma"].cuda(), d["beta"].cuda()
+    sets = []
+    X0, W0 = d["X"].cuda(), d["W"].cuda()
+    for i in range(n_sets):
+        X = X0 if i == 0 else X0.clone()
+        W = W0 if i == 0 else W0.clone()
+        sets.append((X, W, torch.empty((M, N), dtype=X0.dtype, device="cuda")))
+    eps = d["eps"]
+
+    def step(i):
+        X, W, Y = sets[i % n_sets]
+        B.ff_fused_linear_gelu_ln(X, W, b, gamma, beta, eps, Y=Y)
+
+    for i in range(args.warmup):
+        step(i)
+    B.ff_check_device()
+    torch.cuda.synchronize()
+    ev0 = torch.cuda.Event(enable_timing=True)
+    ev1 = torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    ev0.record()
+    for i in range(args.steps):
+        step(i)
+    ev1.record()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    B.ff_check_device()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    ms_kernel = ev0.elapsed_time(ev1) / args.steps
+    variant = B.ff_last_variant()
+
+    hbm_bound = args.workload == "cfg3"
+    if hbm_bound:
+        value = abytes / (ms_per_step * 1e-3) / 1e9
+        unit = "GB/s"
+        roof = {"bound": "hbm", "achieved": abytes / (ms_kernel * 1e-3) / 1e9, "peak": PEAK_HBM_GBS,
+                "unit": "GB/s"}
+    else:
+        value = flops / (ms_per_step * 1e-3) / 1e12
+        unit = "TFLOP/s"
+        peak = PEAK_F32_TFLOPS if wl.dtype == "f32" else PEAK_BF16_TFLOPS
+        roof = {"bound": "mfma", "achieved": flops / (ms_kernel * 1e-3) / 1e12, "peak": peak,
+                "unit": "TFLOP/s"}
+    roof["frac"] = roof["achieved"] / roof["peak"]
+    roof["traffic"] = None
+    roof["kernel_ms"] = ms_kernel
+
+    out = {
+        "metric": "TFLOP/s and % of bf16 MFMA peak (GB/s for small-M) for fused linear+GELU+LN",
+        "value": value, "unit": unit, "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "bf16" if wl.dtype == "bf16" else "f32", "data": "synthetic",
+        "config": {"workload": "%s: %s fused linear+GELU+LayerNorm M=%d K=%d N=%d" % (wl.name, wl.dtype, M, K, N),
+                   "variant": variant, "buffer_sets": n_sets,
+                   "gflop_per_step": flops / 1e9, "algorithmic_mb_per_step": abytes / 1e6},
+        "roofline": roof,
+    }
+
+    if not args.no_eager:
+        import torch.nn.functional as F
+        X, W, _ = sets[0]
+
+        def eager(i):
+            X, W, _ = sets[i % n_sets]
+            return F.layer_norm(F.gelu(F.linear(X, W, b)), (N,), gamma, beta, eps)
+
+        n_e = max(5, args.steps // 4)
+        for i in range(5):
+            eager(i)
+        torch.cuda.synchronize()
+        e0 = time.perf_counter()
+        for i in range(n_e):
+            eager(i)
+        torch.cuda.synchronize()
+        e_ms = (time.perf_counter() - e0) * 1e3 / n_e
+        out["pytorch_eager"] = {"ms_per_step": e_ms, "speedup_of_fused": e_ms / ms_per_step,
+                                "note": "unfused layer_norm(gelu(linear())) in the same dtype on the same GPU"}
+
+    if not args.no_cpu_baseline:
+        import numpy as np
+        import oracle
+        arrs = [d[k].float().numpy() for k in ("X", "W", "b", "gamma", "beta")]
+        threads = oracle.num_threads()
+        probe = min(M, threads)
+        c0 = time.perf_counter()
+        oracle.fused_linear_gelu_ln(*arrs, eps, rows=list(range(probe)))
+        rows_per_s = probe / max(time.perf_counter() - c0, 1e-9)
+        n_rows = max(1, min(M, max(probe, int(args.cpu_seconds * rows_per_s))))
+        rows = np.linspace(0, M - 1, n_rows).astype(np.int64)
+        c0 = time.perf_counter()
+        oracle.fused_linear_gelu_ln(*arrs, eps, rows=rows)
+        c_s = time.perf_counter() - c0
+        frac = n_rows / M
+        if hbm_bound:
+            c_val, c_unit = abytes * frac / c_s / 1e9, "GB/s"
+        else:
+            c_val, c_unit = flops * frac / c_s / 1e12, "TFLOP/s"
+        out["cpu_baseline"] = {"value": c_val, "unit": c_unit, "cores": threads, "kind": "oracle",
+                               "sample": "%d of %d rows (complete rows, all N columns) in %.1f s; rate scaled to the full matrix"
+                                         % (n_rows, M, c_s)}
+    print(json.dumps(out))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

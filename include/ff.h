@@ -1,0 +1,150 @@
+/*
+ * ff — fused linear + erf-GELU + LayerNorm for AMD MI355X (gfx950), C ABI.
+ *
+ *     Y = LayerNorm_N( GELU( X * W^T + b ) ) * gamma + beta
+ *
+ * The operation is the fused operator chain the paper's optimisation loop
+ * targets: a GEMM whose epilogue (bias, activation, row statistic) stays in
+ * registers instead of round-tripping through global memory (App. B.1, the
+ * fused Linear -> row-mean -> GELU epilogue case; Sec. 4, shuffle-based row
+ * reductions and removal of the second global read).  Its semantics are those
+ * of the PyTorch reference operators the paper measures against (Sec. 2.1:
+ * "functionally equivalent to its PyTorch reference"; Sec. 2.2, correctness
+ * test on the same inputs within a small tolerance):
+ *     z[m][n] = b[n] + sum_k X[m][k] * W[n][k]
+ *     g       = 0.5 * z * (1 + erf(z / sqrt 2))
+ *     y[m][n] = (g - mean_n g) / sqrt(var_n g + eps) * gamma[n] + beta[n]
+ * with the biased variance (divide by N) and eps inside the square root.
+ *
+ * Conventions for every entry point
+ *   - All tensor pointers are DEVICE pointers owned by the caller, row-major,
+ *     contiguous, 16-byte aligned.  X is [M,K], W is [N,K] (out-features by
+ *     in-features), b / gamma / beta are [N], Y is [M,N].
+ *   - All tensors share `dtype`: FF_F32 (fp32 in, fp32 accumulate, fp32 out) or
+ *     FF_BF16 (bf16 in, fp32 accumulate and fp32 epilogue, bf16 out rounded to
+ *     nearest even).  Nothing between the GEMM and the final store is rounded
+ *     to bf16.
+ *   - b, gamma, beta may each be NULL, meaning 0, 1, 0.
+ *   - Shapes: M >= 1 arbitrary; bf16 needs K % 8 == 0 and N % 8 == 0, fp32 needs
+ *     K % 4 == 0 and N % 4 == 0 (16-byte rows); anything else returns
+ *     FF_ERR_UNSUPPORTED.  There is no fallback to any library GEMM or
+ *     LayerNorm: the paper's audit of library fallbacks posing as custom
+ *     kernels (Sec. 5, App. C) is the reason.
+ *   - Calls are asynchronous on `stream` (a hipStream_t passed as void*; NULL is
+ *     the default stream).  No host synchronisation is performed.  Y must not
+ *     alias any input.  NaN / Inf propagate; nothing is checked on device.
+ *   - Return value: FF_OK or an ff_status error code.  On error no kernel has
+ *     been launched.
+ *   - Scratch memory ("workspace") holds per-tile row statistics and arrival
+ *     counters (and, for the two-pass variant only, an fp32 copy of G).  If no
+ *     workspace is bound the library allocates one per device on first use and
+ *     grows it when needed (growing synchronises the device).  Calls that share
+ *     a workspace must not overlap in time: use one stream, or bind distinct
+ *     workspaces serially.
+ */
+#ifndef FF_H
+#define FF_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum { FF_F32 = 0, FF_BF16 = 1 } ff_dtype;
+
+typedef enum {
+    FF_OK = 0,
+    FF_ERR_NULL = 1,        /* a required pointer is NULL */
+    FF_ERR_SHAPE = 2,       /* M, K or N not positive, or too large */
+    FF_ERR_DTYPE = 3,       /* dtype is neither FF_F32 nor FF_BF16 */
+    FF_ERR_ALIGN = 4,       /* a pointer is not 16-byte aligned */
+    FF_ERR_UNSUPPORTED = 5, /* K or N not a multiple of the 16-byte vector; or a
+                               forced variant cannot run this shape */
+    FF_ERR_WORKSPACE = 6,   /* bound workspace too small / allocation failed */
+    FF_ERR_LAUNCH = 7,      /* the HIP runtime refused the launch */
+    FF_ERR_DEVICE = 8       /* a kernel reported a failed cross-tile wait */
+} ff_status;
+
+/* Kernel variants (for ff_debug_force_variant and ff_last_variant). */
+typedef enum {
+    FF_VARIANT_AUTO = 0,
+    FF_VARIANT_TILED_FUSED = 1,   /* MFMA tiles; row statistics merged across
+                                     tiles inside the launch, G stays in registers */
+    FF_VARIANT_TILED_TWOPASS = 2, /* MFMA tiles write fp32 G + statistics; a second
+                                     kernel normalises (used when a row spans more
+                                     tiles than can be co-resident) */
+    FF_VARIANT_SMALL_M = 3        /* M <= 32, bf16: streams W once at HBM rate */
+} ff_variant;
+
+/*
+ * The fused operator.  Implements the chain above;
+ * see the file header for argument meaning, layout, ownership and errors.
+ *   X, W: required.  b, gamma, beta: optional (NULL).  Y: required, written.
+ *   eps: added to the variance inside the square root.
+ *   dtype: an ff_dtype.  stream: hipStream_t.
+ */
+int ff_fused_linear_gelu_ln(const void *X, const void *W, const void *b,
+                            const void *gamma, const void *beta, float eps,
+                            int64_t M, int64_t K, int64_t N, int dtype,
+                            void *Y, void *stream);
+
+/*
+ * Bytes of workspace a call with this shape needs under the current variant
+ * selection (0 on invalid arguments).  Pure host arithmetic.
+ */
+size_t ff_workspace_bytes(int64_t M, int64_t K, int64_t N, int dtype);
+
+/*
+ * Bind caller-owned device memory (256-byte aligned) as the workspace of the
+ * current device, or unbind with (NULL, 0), after which the library allocates
+ * its own again.  The first call after binding clears the control region of the
+ * workspace with hipMemsetAsync on that call's stream.  The memory must stay
+ * valid until unbound and all work using it has completed.
+ */
+int ff_set_workspace(void *dev_ptr, size_t bytes);
+
+/*
+ * Synchronise `stream`, then report whether any kernel since the last check
+ * gave up waiting for the other tiles of its rows (FF_ERR_DEVICE) — which can
+ * only happen if the launch's workgroups were not co-resident — and clear that
+ * state.  FF_OK otherwise.
+ */
+int ff_check_device(void *stream);
+
+/* Human-readable name of an ff_status value (static storage). */
+const char *ff_status_string(int status);
+
+/* Library version: major * 10000 + minor * 100 + patch. */
+int ff_version(void);
+
+/* The variant the most recent successful ff_fused_linear_gelu_ln call on this
+ * host thread's device used (an ff_variant), or 0 if none yet. */
+int ff_last_variant(void);
+
+/* ---- test hooks: exported for the parity tests, not part of the product API ---- */
+
+/*
+ * Linear stage only (GEMM + bias) through the tiled MFMA core, fp32 result:
+ * Z_f32[m][n] = b[n] + sum_k X[m][k] W[n][k].  Z_f32 is a device pointer to
+ * M*N floats.  With integer-valued inputs of small magnitude the result is
+ * exact, which pins the GEMM core independently of any tolerance.
+ */
+int ff_debug_linear(const void *X, const void *W, const void *b,
+                    int64_t M, int64_t K, int64_t N, int dtype,
+                    float *Z_f32, void *stream);
+
+/* Force a variant for later calls (FF_VARIANT_AUTO restores selection by shape).
+ * A forced variant that cannot run a shape makes the call return
+ * FF_ERR_UNSUPPORTED; it never silently runs something else. */
+int ff_debug_force_variant(int variant);
+
+/* Upper bound, in microseconds, a workgroup waits for the other tiles of its
+ * rows before it gives up and flags FF_ERR_DEVICE (default 2,000,000). */
+int ff_debug_set_wait_limit_us(int64_t microseconds);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FF_H */

@@ -1,0 +1,170 @@
+"""ctypes binding of libff.so: the same entry points as include/ff.h, taking
+torch tensors.  Argument marshalling only — every step of the operator runs in
+the HIP kernels.  There is no CPU or library fallback: if the extension is not
+built, loading raises."""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional
+
+import torch
+
+from .build import LIB_PATH
+
+FF_F32, FF_BF16 = 0, 1
+FF_OK = 0
+FF_VARIANT_AUTO, FF_VARIANT_TILED_FUSED, FF_VARIANT_TILED_TWOPASS, FF_VARIANT_SMALL_M = 0, 1, 2, 3
+
+EXPORTS = [
+    "ff_fused_linear_gelu_ln", "ff_workspace_bytes", "ff_set_workspace", "ff_check_device",
+    "ff_status_string", "ff_version", "ff_last_variant", "ff_debug_linear",
+    "ff_debug_force_variant", "ff_debug_set_wait_limit_us",
+]
+
+_lib = None
+
+
+class FFError(RuntimeError):
+    def __init__(self, status: int):
+        self.status = status
+        super().__init__(ff_status_string(status))
+
+
+def load() -> ctypes.CDLL:
+    """Load libff.so (built beforehand by build.build_library / __graft_entry__.build)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(
+                "%s is missing: build it with `python -m paper_2511_01884_amd.build`; "
+                "there is no fallback path" % LIB_PATH)
+        lib = ctypes.CDLL(LIB_PATH)
+        vp, i64, ci = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int
+        lib.ff_fused_linear_gelu_ln.restype = ci
+        lib.ff_fused_linear_gelu_ln.argtypes = [vp, vp, vp, vp, vp, ctypes.c_float, i64, i64, i64, ci, vp, vp]
+        lib.ff_workspace_bytes.restype = ctypes.c_size_t
+        lib.ff_workspace_bytes.argtypes = [i64, i64, i64, ci]
+        lib.ff_set_workspace.restype = ci
+        lib.ff_set_workspace.argtypes = [vp, ctypes.c_size_t]
+        lib.ff_check_device.restype = ci
+        lib.ff_check_device.argtypes = [vp]
+        lib.ff_status_string.restype = ctypes.c_char_p
+        lib.ff_status_string.argtypes = [ci]
+        lib.ff_version.restype = ci
+        lib.ff_last_variant.restype = ci
+        lib.ff_debug_linear.restype = ci
+        lib.ff_debug_linear.argtypes = [vp, vp, vp, i64, i64, i64, ci, vp, vp]
+        lib.ff_debug_force_variant.restype = ci
+        lib.ff_debug_force_variant.argtypes = [ci]
+        lib.ff_debug_set_wait_limit_us.restype = ci
+        lib.ff_debug_set_wait_limit_us.argtypes = [i64]
+        _lib = lib
+    return _lib
+
+
+def _dtype_code(t: torch.Tensor) -> int:
+    if t.dtype == torch.float32:
+        return FF_F32
+    if t.dtype == torch.bfloat16:
+        return FF_BF16
+    raise TypeError("tensors must be float32 or bfloat16")
+
+
+def _ptr(t: Optional[torch.Tensor], like: Optional[torch.Tensor] = None):
+    if t is None:
+        return None
+    if not t.is_cuda or not t.is_contiguous():
+        raise ValueError("tensors must be contiguous device tensors")
+    if like is not None and (t.dtype != like.dtype or t.device != like.device):
+        raise ValueError("all tensors must share dtype and device")
+    return ctypes.c_void_p(t.data_ptr())
+
+
+def _stream(stream) -> ctypes.c_void_p:
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return ctypes.c_void_p(stream.cuda_stream if hasattr(stream, "cuda_stream") else int(stream))
+
+
+def ff_status_string(status: int) -> str:
+    return load().ff_status_string(int(status)).decode()
+
+
+def ff_version() -> int:
+    return int(load().ff_version())
+
+
+def ff_last_variant() -> int:
+    return int(load().ff_last_variant())
+
+
+def ff_workspace_bytes(M: int, K: int, N: int, dtype: int) -> int:
+    return int(load().ff_workspace_bytes(M, K, N, dtype))
+
+
+def ff_set_workspace(buf: Optional[torch.Tensor]) -> None:
+    if buf is None:
+        rc = load().ff_set_workspace(None, 0)
+    else:
+        rc = load().ff_set_workspace(ctypes.c_void_p(buf.data_ptr()), buf.numel() * buf.element_size())
+    if rc != FF_OK:
+        raise FFError(rc)
+
+
+def ff_check_device(stream=None) -> None:
+    rc = load().ff_check_device(_stream(stream))
+    if rc != FF_OK:
+        raise FFError(rc)
+
+
+def ff_debug_force_variant(variant: int) -> None:
+    rc = load().ff_debug_force_variant(int(variant))
+    if rc != FF_OK:
+        raise FFError(rc)
+
+
+def ff_debug_set_wait_limit_us(us: int) -> None:
+    rc = load().ff_debug_set_wait_limit_us(int(us))
+    if rc != FF_OK:
+        raise FFError(rc)
+
+
+def ff_fused_linear_gelu_ln(X: torch.Tensor, W: torch.Tensor, b: Optional[torch.Tensor],
+                            gamma: Optional[torch.Tensor], beta: Optional[torch.Tensor],
+                            eps: float, Y: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+    """Y = LayerNorm_N(GELU(X W^T + b)) * gamma + beta on the device of X.
+    Allocates Y with torch if not given; everything else happens in libff.so."""
+    if X.dim() != 2 or W.dim() != 2 or X.shape[1] != W.shape[1]:
+        raise ValueError("X must be [M,K] and W [N,K]")
+    M, K = X.shape
+    N = W.shape[0]
+    for v in (b, gamma, beta):
+        if v is not None and tuple(v.shape) != (N,):
+            raise ValueError("b, gamma, beta must have shape [N]")
+    if Y is None:
+        Y = torch.empty((M, N), dtype=X.dtype, device=X.device)
+    elif tuple(Y.shape) != (M, N):
+        raise ValueError("Y must be [M,N]")
+    with torch.cuda.device(X.device):
+        rc = load().ff_fused_linear_gelu_ln(_ptr(X), _ptr(W, X), _ptr(b, X), _ptr(gamma, X),
+                                            _ptr(beta, X), float(eps), M, K, N, _dtype_code(X),
+                                            _ptr(Y, X), _stream(stream))
+    if rc != FF_OK:
+        raise FFError(rc)
+    return Y
+
+
+def ff_debug_linear(X: torch.Tensor, W: torch.Tensor, b: Optional[torch.Tensor],
+                    Z: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+    """fp32 Z = X W^T + b through the tiled MFMA core (test hook)."""
+    M, K = X.shape
+    N = W.shape[0]
+    if Z is None:
+        Z = torch.empty((M, N), dtype=torch.float32, device=X.device)
+    with torch.cuda.device(X.device):
+        rc = load().ff_debug_linear(_ptr(X), _ptr(W, X), _ptr(b, X), M, K, N, _dtype_code(X),
+                                    ctypes.c_void_p(Z.data_ptr()), _stream(stream))
+    if rc != FF_OK:
+        raise FFError(rc)
+    return Z

@@ -1,0 +1,368 @@
+// Host side of the C ABI declared in include/ff.h: argument validation, variant
+// selection by shape, workspace management and kernel launches.  Nothing here
+// computes on tensors and nothing falls back to a library GEMM or LayerNorm.
+#include <mutex>
+
+#include "../../include/ff.h"
+#include "ff_tile.hpp"
+
+namespace {
+
+using namespace ff;
+
+constexpr int kMaxDevices = 64;
+
+struct DeviceState {
+    bool probed = false;
+    int num_cus = 256;
+    long long ticks_per_us = 100;
+    void *ws = nullptr;       // bound or owned workspace
+    size_t ws_bytes = 0;
+    bool ws_owned = false;
+    bool ws_clean = false;    // control region zeroed since (re)binding
+};
+
+std::mutex g_mutex;
+DeviceState g_dev[kMaxDevices];
+int g_forced_variant = FF_VARIANT_AUTO;
+long long g_wait_limit_us = 2000000;
+thread_local int t_last_variant = 0;
+
+struct Plan {
+    int variant = 0;
+    int tile = 0;      // BM = BN of the tiled variants
+    int NT = 0, RB = 0;
+    int grid = 0, rounds = 0, swz_sc = 0;
+    int mt = 0, strips = 0;  // small-M
+    size_t partial_off = 0, partial_bytes = 0;
+    size_t g_off = 0, g_bytes = 0;
+    size_t total_bytes = 0;
+};
+
+size_t round_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+int validate_shape(int64_t M, int64_t K, int64_t N, int dtype)
+{
+    if (dtype != FF_F32 && dtype != FF_BF16)
+        return FF_ERR_DTYPE;
+    if (M <= 0 || K <= 0 || N <= 0)
+        return FF_ERR_SHAPE;
+    if (M > (int64_t)1 << 30 || K > (int64_t)1 << 30 || N > (int64_t)1 << 30)
+        return FF_ERR_SHAPE;
+    const int vec = dtype == FF_BF16 ? 8 : 4;
+    if (K % vec != 0 || N % vec != 0)
+        return FF_ERR_UNSUPPORTED;
+    return FF_OK;
+}
+
+// Decides variant, tile size, grid and workspace layout for a shape.
+int make_plan(int64_t M, int64_t K, int64_t N, int dtype, int num_cus, int forced, bool linear_only,
+              Plan &pl)
+{
+    (void)K;
+    const bool bf16 = dtype == FF_BF16;
+    const int64_t strips = (N + kSmallMStripCols - 1) / kSmallMStripCols;
+    const bool smallm_ok = bf16 && M <= 32 && strips <= (int64_t)num_cus * kSmallMMaxStripsPerGroup;
+
+    int variant = forced;
+    if (linear_only)
+        variant = FF_VARIANT_TILED_TWOPASS;  // layout only; the launch uses the linear-only mode
+    else if (variant == FF_VARIANT_AUTO)
+        variant = smallm_ok ? FF_VARIANT_SMALL_M : 0;
+
+    if (variant == FF_VARIANT_SMALL_M) {
+        if (!smallm_ok)
+            return FF_ERR_UNSUPPORTED;
+        pl.variant = FF_VARIANT_SMALL_M;
+        pl.mt = M <= 16 ? 1 : 2;
+        pl.strips = (int)strips;
+        pl.grid = (int)(strips < num_cus ? strips : num_cus);
+        pl.partial_off = kCtrlBytes;
+        pl.partial_bytes = round_up((size_t)strips * 16 * pl.mt * sizeof(float) * 2, 256);
+        pl.total_bytes = pl.partial_off + pl.partial_bytes;
+        return FF_OK;
+    }
+
+    // tiled variants: 256x256 tiles unless they would leave most of the chip idle
+    const int64_t tiles256 = ((M + 255) / 256) * ((N + 255) / 256);
+    pl.tile = tiles256 * 2 >= num_cus ? 256 : 128;
+    const int64_t RB = (M + pl.tile - 1) / pl.tile;
+    const int64_t NT = (N + pl.tile - 1) / pl.tile;
+    if (RB > kMaxRowBlocks || RB * NT > (int64_t)1 << 30)
+        return FF_ERR_SHAPE;
+    pl.RB = (int)RB;
+    pl.NT = (int)NT;
+    const int64_t total = RB * NT;
+    pl.grid = (int)(total < num_cus ? total : num_cus);
+    pl.rounds = (int)((total + pl.grid - 1) / pl.grid);
+    const bool fused_ok = NT <= pl.grid;
+    if (variant == 0)
+        variant = fused_ok ? FF_VARIANT_TILED_FUSED : FF_VARIANT_TILED_TWOPASS;
+    if (variant == FF_VARIANT_TILED_FUSED && !fused_ok)
+        return FF_ERR_UNSUPPORTED;
+    if (variant != FF_VARIANT_TILED_FUSED && variant != FF_VARIANT_TILED_TWOPASS)
+        return FF_ERR_UNSUPPORTED;
+    pl.variant = variant;
+    // XCD-aware tile order: needs 8 XCDs x 32 workgroups and NT dividing the grid
+    pl.swz_sc = 0;
+    if (pl.grid == 256 && NT <= 256 && (256 % NT) == 0) {
+        int sc = (int)(NT / 8 > 8 ? NT / 8 : 8);
+        if (sc > NT)
+            sc = (int)NT;
+        pl.swz_sc = sc;
+    }
+    pl.partial_off = kCtrlBytes;
+    pl.partial_bytes = round_up((size_t)total * pl.tile * sizeof(float) * 2, 256);
+    pl.g_off = pl.partial_off + pl.partial_bytes;
+    pl.g_bytes = (variant == FF_VARIANT_TILED_TWOPASS && !linear_only)
+                     ? round_up((size_t)M * (size_t)N * sizeof(float), 256)
+                     : 0;
+    pl.total_bytes = pl.g_off + pl.g_bytes;
+    return FF_OK;
+}
+
+DeviceState *current_device_state(int *dev_out = nullptr)
+{
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) {
+        (void)hipGetLastError();
+        return nullptr;
+    }
+    DeviceState &st = g_dev[dev];
+    if (!st.probed) {
+        int v = 0;
+        if (hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && v > 0)
+            st.num_cus = v;
+        if (hipDeviceGetAttribute(&v, hipDeviceAttributeWallClockRate, dev) == hipSuccess && v > 0)
+            st.ticks_per_us = v / 1000 > 0 ? v / 1000 : 1;
+        (void)hipGetLastError();
+        st.probed = true;
+    }
+    if (dev_out)
+        *dev_out = dev;
+    return &st;
+}
+
+// Makes sure a workspace of at least `bytes` exists and its control region is zero.
+int prepare_workspace(DeviceState &st, size_t bytes, hipStream_t stream)
+{
+    if (st.ws == nullptr || (st.ws_owned && st.ws_bytes < bytes)) {
+        if (st.ws != nullptr) {
+            (void)hipDeviceSynchronize();
+            (void)hipFree(st.ws);
+            st.ws = nullptr;
+        }
+        const size_t want = round_up(bytes + bytes / 4, 1 << 20);
+        if (hipMalloc(&st.ws, want) != hipSuccess) {
+            (void)hipGetLastError();
+            st.ws = nullptr;
+            st.ws_bytes = 0;
+            return FF_ERR_WORKSPACE;
+        }
+        st.ws_bytes = want;
+        st.ws_owned = true;
+        st.ws_clean = false;
+    }
+    if (st.ws_bytes < bytes)
+        return FF_ERR_WORKSPACE;
+    if (!st.ws_clean) {
+        if (hipMemsetAsync(st.ws, 0, kCtrlBytes, stream) != hipSuccess) {
+            (void)hipGetLastError();
+            return FF_ERR_LAUNCH;
+        }
+        st.ws_clean = true;
+    }
+    return FF_OK;
+}
+
+bool misaligned(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) != 0; }
+
+int run(const void *X, const void *W, const void *b, const void *gamma, const void *beta, float eps,
+        int64_t M, int64_t K, int64_t N, int dtype, void *Y, float *Z, bool linear_only,
+        hipStream_t stream)
+{
+    int rc = validate_shape(M, K, N, dtype);
+    if (rc != FF_OK)
+        return rc;
+    if (!X || !W || (!linear_only && !Y) || (linear_only && !Z))
+        return FF_ERR_NULL;
+    if (misaligned(X) || misaligned(W) || misaligned(b) || misaligned(gamma) || misaligned(beta) ||
+        misaligned(Y) || misaligned(Z))
+        return FF_ERR_ALIGN;
+
+    std::lock_guard<std::mutex> lock(g_mutex);
+    DeviceState *st = current_device_state();
+    if (!st)
+        return FF_ERR_LAUNCH;
+    Plan pl;
+    rc = make_plan(M, K, N, dtype, st->num_cus, g_forced_variant, linear_only, pl);
+    if (rc != FF_OK)
+        return rc;
+    rc = prepare_workspace(*st, pl.total_bytes, stream);
+    if (rc != FF_OK)
+        return rc;
+
+    char *ws = static_cast<char *>(st->ws);
+    unsigned *err = reinterpret_cast<unsigned *>(ws);
+    unsigned *counters = reinterpret_cast<unsigned *>(ws + kCounterOffset);
+    const long long wait_ticks = g_wait_limit_us * st->ticks_per_us;
+    const bool bf16 = dtype == FF_BF16;
+
+    if (pl.variant == FF_VARIANT_SMALL_M) {
+        SmallMParams p{};
+        p.X = X; p.W = W; p.b = b; p.gamma = gamma; p.beta = beta; p.Y = Y;
+        p.partials = reinterpret_cast<floatx2 *>(ws + pl.partial_off);
+        p.counters = counters;
+        p.err = err;
+        p.eps = eps;
+        p.M = (int)M; p.K = (int)K; p.N = (int)N;
+        p.strips = pl.strips;
+        p.wait_ticks = wait_ticks;
+        if (launch_smallm_kernel(pl.mt, p, pl.grid, stream) != hipSuccess)
+            return FF_ERR_LAUNCH;
+        t_last_variant = pl.variant;
+        return FF_OK;
+    }
+
+    TileParams p{};
+    p.X = X; p.W = W; p.b = b; p.gamma = gamma; p.beta = beta; p.Y = Y;
+    p.F = linear_only ? Z : reinterpret_cast<float *>(ws + pl.g_off);
+    p.partials = reinterpret_cast<floatx2 *>(ws + pl.partial_off);
+    p.counters = counters;
+    p.err = err;
+    p.eps = eps;
+    p.M = (int)M; p.K = (int)K; p.N = (int)N;
+    p.NT = pl.NT; p.RB = pl.RB; p.rounds = pl.rounds; p.swz_sc = pl.swz_sc;
+    p.wait_ticks = wait_ticks;
+    const int mode = linear_only ? kLinearOnly
+                                 : (pl.variant == FF_VARIANT_TILED_FUSED ? kFused : kTwoPass);
+    if (launch_tile_kernel(bf16, pl.tile, mode, p, pl.grid, stream) != hipSuccess)
+        return FF_ERR_LAUNCH;
+    if (mode == kTwoPass) {
+        FinalizeParams f{};
+        f.G = p.F; f.partials = p.partials; f.gamma = gamma; f.beta = beta; f.Y = Y;
+        f.eps = eps; f.M = (int)M; f.N = (int)N; f.NT = pl.NT; f.BM = pl.tile; f.BN = pl.tile;
+        if (launch_finalize_kernel(bf16, f, stream) != hipSuccess)
+            return FF_ERR_LAUNCH;
+    }
+    if (!linear_only)
+        t_last_variant = pl.variant;
+    return FF_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int ff_fused_linear_gelu_ln(const void *X, const void *W, const void *b, const void *gamma,
+                            const void *beta, float eps, int64_t M, int64_t K, int64_t N, int dtype,
+                            void *Y, void *stream)
+{
+    return run(X, W, b, gamma, beta, eps, M, K, N, dtype, Y, nullptr, false,
+               static_cast<hipStream_t>(stream));
+}
+
+int ff_debug_linear(const void *X, const void *W, const void *b, int64_t M, int64_t K, int64_t N,
+                    int dtype, float *Z_f32, void *stream)
+{
+    return run(X, W, b, nullptr, nullptr, 0.0f, M, K, N, dtype, nullptr, Z_f32, true,
+               static_cast<hipStream_t>(stream));
+}
+
+size_t ff_workspace_bytes(int64_t M, int64_t K, int64_t N, int dtype)
+{
+    if (validate_shape(M, K, N, dtype) != FF_OK)
+        return 0;
+    std::lock_guard<std::mutex> lock(g_mutex);
+    DeviceState *st = current_device_state();
+    const int num_cus = st ? st->num_cus : 256;
+    Plan pl;
+    if (make_plan(M, K, N, dtype, num_cus, g_forced_variant, false, pl) != FF_OK)
+        return 0;
+    return pl.total_bytes;
+}
+
+int ff_set_workspace(void *dev_ptr, size_t bytes)
+{
+    std::lock_guard<std::mutex> lock(g_mutex);
+    DeviceState *st = current_device_state();
+    if (!st)
+        return FF_ERR_LAUNCH;
+    if (dev_ptr != nullptr && ((reinterpret_cast<uintptr_t>(dev_ptr) & 255u) != 0))
+        return FF_ERR_ALIGN;
+    if (dev_ptr != nullptr && bytes < kCtrlBytes)
+        return FF_ERR_WORKSPACE;
+    if (st->ws != nullptr && st->ws_owned) {
+        (void)hipDeviceSynchronize();
+        (void)hipFree(st->ws);
+    }
+    st->ws = dev_ptr;
+    st->ws_bytes = dev_ptr ? bytes : 0;
+    st->ws_owned = false;
+    st->ws_clean = false;
+    return FF_OK;
+}
+
+int ff_check_device(void *stream)
+{
+    std::lock_guard<std::mutex> lock(g_mutex);
+    DeviceState *st = current_device_state();
+    if (!st)
+        return FF_ERR_LAUNCH;
+    if (hipStreamSynchronize(static_cast<hipStream_t>(stream)) != hipSuccess) {
+        (void)hipGetLastError();
+        return FF_ERR_LAUNCH;
+    }
+    if (st->ws == nullptr || !st->ws_clean)
+        return FF_OK;
+    unsigned flag = 0;
+    if (hipMemcpy(&flag, st->ws, sizeof(flag), hipMemcpyDeviceToHost) != hipSuccess) {
+        (void)hipGetLastError();
+        return FF_ERR_LAUNCH;
+    }
+    if (flag == 0)
+        return FF_OK;
+    // a wait gave up: counters may be half-way; start from a clean control region
+    (void)hipMemset(st->ws, 0, kCtrlBytes);
+    return FF_ERR_DEVICE;
+}
+
+const char *ff_status_string(int status)
+{
+    switch (status) {
+    case FF_OK: return "FF_OK";
+    case FF_ERR_NULL: return "FF_ERR_NULL: a required pointer is NULL";
+    case FF_ERR_SHAPE: return "FF_ERR_SHAPE: M, K and N must be positive and below 2^30";
+    case FF_ERR_DTYPE: return "FF_ERR_DTYPE: dtype must be FF_F32 or FF_BF16";
+    case FF_ERR_ALIGN: return "FF_ERR_ALIGN: pointers must be 16-byte aligned";
+    case FF_ERR_UNSUPPORTED: return "FF_ERR_UNSUPPORTED: K and N must be multiples of 8 (bf16) or 4 (fp32), or the forced variant cannot run this shape";
+    case FF_ERR_WORKSPACE: return "FF_ERR_WORKSPACE: workspace too small or allocation failed";
+    case FF_ERR_LAUNCH: return "FF_ERR_LAUNCH: the HIP runtime refused the request";
+    case FF_ERR_DEVICE: return "FF_ERR_DEVICE: a workgroup gave up waiting for the other tiles of its rows";
+    default: return "unknown ff_status";
+    }
+}
+
+int ff_version(void) { return 100; }
+
+int ff_last_variant(void) { return t_last_variant; }
+
+int ff_debug_force_variant(int variant)
+{
+    if (variant < FF_VARIANT_AUTO || variant > FF_VARIANT_SMALL_M)
+        return FF_ERR_UNSUPPORTED;
+    std::lock_guard<std::mutex> lock(g_mutex);
+    g_forced_variant = variant;
+    return FF_OK;
+}
+
+int ff_debug_set_wait_limit_us(int64_t microseconds)
+{
+    if (microseconds <= 0)
+        return FF_ERR_SHAPE;
+    std::lock_guard<std::mutex> lock(g_mutex);
+    g_wait_limit_us = microseconds;
+    return FF_OK;
+}
+
+}  // extern "C"

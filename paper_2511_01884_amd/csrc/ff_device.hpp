@@ -1,0 +1,121 @@
+// Device-side building blocks shared by the gfx950 kernels: bf16 <-> fp32,
+// erf-form GELU, pairwise merge of (count, mean, M2) row statistics, and the
+// workspace layout the kernels and the host agree on.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace ff {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+typedef float floatx4 __attribute__((ext_vector_type(4)));
+typedef float floatx2 __attribute__((ext_vector_type(2)));
+typedef unsigned int uintx4 __attribute__((ext_vector_type(4)));
+typedef unsigned int uintx2 __attribute__((ext_vector_type(2)));
+
+// ---- workspace layout (bytes from the workspace base) ----------------------
+// [0, 4)                error word: non-zero once a cross-tile wait gave up
+// [256, CTRL_BYTES)     arrival / departure counters, two uint32 per row-block
+// [CTRL_BYTES, ...)     per-tile row statistics (float2 mean, M2), then the
+//                       two-pass variant's fp32 G
+constexpr size_t kCtrlBytes = 1u << 20;
+constexpr size_t kCounterOffset = 256;
+constexpr int64_t kMaxRowBlocks = (int64_t)((kCtrlBytes - kCounterOffset) / 8);
+
+// ---- bf16 <-> fp32 -----------------------------------------------------------
+__device__ __forceinline__ float bf16_bits_to_float(unsigned short h)
+{
+    return __uint_as_float(((unsigned)h) << 16);
+}
+__device__ __forceinline__ float load_as_float(const float *p) { return *p; }
+__device__ __forceinline__ float load_as_float(const __bf16 *p)
+{
+    return bf16_bits_to_float(*reinterpret_cast<const unsigned short *>(p));
+}
+// Round-to-nearest-even pack of two floats (hardware conversion on gfx950).
+__device__ __forceinline__ unsigned pack_bf16x2(float lo, float hi)
+{
+    floatx2 v = {lo, hi};
+    bf16x2 h = __builtin_convertvector(v, bf16x2);
+    return *reinterpret_cast<unsigned *>(&h);
+}
+
+// ---- GELU, erf form -----------------------------------------------------------
+// g = z * Phi(z), Phi(z) = 0.5 * erfc(-z / sqrt 2).  erfc(x), x >= 0, uses the
+// five-term rational-times-Gaussian formula of Abramowitz & Stegun 7.1.26,
+//     erfc(x) ~ (a1 t + a2 t^2 + a3 t^3 + a4 t^4 + a5 t^5) exp(-x^2),  t = 1/(1 + p x),
+// absolute error <= 1.5e-7.  Evaluating the tail directly (instead of 1 + erf)
+// keeps that absolute bound for negative z, where 1 + erf would cancel; the
+// error in g is <= 0.75e-7 * |z|.
+__device__ __forceinline__ float gelu_erf(float z)
+{
+    const float x = fabsf(z) * 0.70710678118654752f;
+    const float t = __frcp_rn(fmaf(0.3275911f, x, 1.0f));
+    float p = 1.061405429f;
+    p = fmaf(p, t, -1.453152027f);
+    p = fmaf(p, t, 1.421413741f);
+    p = fmaf(p, t, -0.284496736f);
+    p = fmaf(p, t, 0.254829592f);
+    p *= t;
+    // exp(-x^2) = 2^(-z^2 * log2(e) / 2)
+    const float e = __builtin_amdgcn_exp2f(z * z * -0.72134752044448170f);
+    const float q = 0.5f * p * e;            // Phi(-|z|)
+    const float phi = z > 0.0f ? 1.0f - q : q;
+    return z * phi;
+}
+
+// ---- (count, mean, M2) merge (Chan et al. pairwise update) ---------------------
+// Folds block b into block a:  delta = mean_b - mean_a; n = n_a + n_b;
+// mean = mean_a + delta * n_b / n;  M2 = M2_a + M2_b + delta^2 * n_a * n_b / n.
+__device__ __forceinline__ void merge_stats(float &na, float &mean_a, float &m2a,
+                                            float nb, float mean_b, float m2b)
+{
+    const float n = na + nb;
+    if (n > 0.0f) {
+        const float inv = 1.0f / n;
+        const float delta = mean_b - mean_a;
+        mean_a = fmaf(delta, nb * inv, mean_a);
+        m2a = m2a + m2b + delta * delta * (na * nb * inv);
+    }
+    na = n;
+}
+
+// Device-scope release / acquire around the cross-workgroup exchange of row
+// statistics: workgroups of one launch run on different XCDs with separate L2s.
+__device__ __forceinline__ void release_device() { __threadfence(); }
+__device__ __forceinline__ void acquire_device() { __threadfence(); }
+
+__device__ __forceinline__ unsigned atomic_add_device(unsigned *p, unsigned v)
+{
+    return __hip_atomic_fetch_add(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ unsigned atomic_load_device(const unsigned *p)
+{
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ void atomic_store_device(unsigned *p, unsigned v)
+{
+    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// Wait (bounded) until *counter >= target.  Returns false if the bound expired.
+// One thread calls this; the rest of the workgroup waits at a barrier.
+__device__ __forceinline__ bool wait_counter(const unsigned *counter, unsigned target,
+                                             long long limit_ticks)
+{
+    if (atomic_load_device(counter) >= target)
+        return true;
+    const long long t0 = wall_clock64();
+    for (;;) {
+        __builtin_amdgcn_s_sleep(4);
+        if (atomic_load_device(counter) >= target)
+            return true;
+        if (wall_clock64() - t0 > limit_ticks)
+            return false;
+    }
+}
+
+}  // namespace ff

@@ -1,0 +1,61 @@
+// Host/device interface of the kernels: parameter blocks and launch functions.
+#pragma once
+#include <type_traits>
+
+#include "ff_device.hpp"
+
+namespace ff {
+
+enum { kFused = 0, kTwoPass = 1, kLinearOnly = 2 };
+
+struct TileParams {
+    const void *X;       // [M,K]
+    const void *W;       // [N,K]
+    const void *b;       // [N] or null
+    const void *gamma;   // [N] or null
+    const void *beta;    // [N] or null
+    void *Y;             // kFused: [M,N] in the tensor dtype
+    float *F;            // kTwoPass: fp32 G scratch [M,N]; kLinearOnly: fp32 Z out
+    floatx2 *partials;   // [RB][NT][BM] (mean, M2) per tile row
+    unsigned *counters;  // [RB][2] arrival, departure
+    unsigned *err;       // error word
+    float eps;
+    int M, K, N;
+    int NT;              // tiles along N
+    int RB;              // row-blocks
+    int rounds;          // ceil(RB * NT / grid)
+    int swz_sc;          // XCD-aware order: super-block width in tiles, 0 = plain order
+    long long wait_ticks;
+};
+
+struct FinalizeParams {
+    const float *G;
+    const floatx2 *partials;
+    const void *gamma;
+    const void *beta;
+    void *Y;
+    float eps;
+    int M, N, NT, BM, BN;
+};
+
+struct SmallMParams {
+    const void *X, *W, *b, *gamma, *beta;
+    void *Y;
+    floatx2 *partials;   // [strips][16 * MT] (mean, M2)
+    unsigned *counters;  // [2]
+    unsigned *err;
+    float eps;
+    int M, K, N;
+    int strips;          // N / 32 rounded up
+    long long wait_ticks;
+};
+
+hipError_t launch_tile_kernel(bool bf16, int tile, int mode, const TileParams &p, int grid,
+                              hipStream_t stream);
+hipError_t launch_finalize_kernel(bool bf16, const FinalizeParams &p, hipStream_t stream);
+hipError_t launch_smallm_kernel(int mt, const SmallMParams &p, int grid, hipStream_t stream);
+
+constexpr int kSmallMStripCols = 32;
+constexpr int kSmallMMaxStripsPerGroup = 8;
+
+}  // namespace ff

@@ -1,0 +1,213 @@
+"""GPU parity tests: the HIP library against the fp64 CPU oracle on the same
+seeded inputs, element by element (small and ragged shapes), on sampled rows at
+the full benchmark sizes, plus the edge cases and invariants of the method."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2511_01884_amd import binding as B
+from paper_2511_01884_amd.inputs import (CONFIGS, make_inputs, make_integer_inputs, sample_rows)
+from parity_util import check_against_oracle, gpu_run, oracle_on, to_np32
+
+pytestmark = pytest.mark.gpu
+
+AUTO, FUSED, TWOPASS, SMALLM = (B.FF_VARIANT_AUTO, B.FF_VARIANT_TILED_FUSED,
+                                B.FF_VARIANT_TILED_TWOPASS, B.FF_VARIANT_SMALL_M)
+
+
+def _announce(*a):
+    print("[case]", *a, flush=True)
+
+
+# ------------------------------------------------------------ element by element
+SMALL_CASES = [
+    # (M, K, N, dtype, variant, expected variant)
+    (256, 512, 512, "f32", AUTO, FUSED),        # the fp32 parity workload
+    (256, 512, 512, "f32", TWOPASS, TWOPASS),
+    (77, 36, 132, "f32", AUTO, FUSED),          # ragged M, K, N; 128-tiles
+    (300, 200, 520, "bf16", AUTO, FUSED),       # ragged everything, K tail of 8
+    (300, 200, 520, "bf16", TWOPASS, TWOPASS),
+    (129, 64, 8, "bf16", AUTO, FUSED),          # one 8-column tile
+    (1, 8, 8, "bf16", FUSED, FUSED),            # smallest legal shape, tiled path
+    (2085, 264, 4088, "bf16", AUTO, FUSED),     # 256-tiles, 9 x 16 tiles, ragged
+    (2085, 264, 4088, "bf16", TWOPASS, TWOPASS),
+    (2100, 96, 2048, "f32", AUTO, FUSED),       # fp32 on 256-tiles
+    (40, 128, 1024, "bf16", AUTO, FUSED),       # just above the small-M limit
+]
+
+
+@pytest.mark.parametrize("M,K,N,dtype,variant,expect", SMALL_CASES)
+def test_full_matrix_parity(M, K, N, dtype, variant, expect):
+    _announce("full", M, K, N, dtype, variant)
+    d = make_inputs(M, K, N, dtype, seed=11)
+    Y, used = gpu_run(d, variant)
+    assert used == expect
+    stats = check_against_oracle(Y, oracle_on(d), dtype, "%dx%dx%d" % (M, K, N))
+    print(stats)
+
+
+SMALLM_CASES = [(16, 8192, 8192), (16, 1024, 1024), (5, 520, 1000), (32, 1024, 2048),
+                (17, 72, 40), (1, 8, 8), (16, 4096, 32768), (9, 256, 16384 + 64)]
+
+
+@pytest.mark.parametrize("M,K,N", SMALLM_CASES)
+def test_small_m_streamer_parity(M, K, N):
+    _announce("small-m", M, K, N)
+    d = make_inputs(M, K, N, "bf16", seed=12)
+    Y, used = gpu_run(d, AUTO)
+    assert used == SMALLM
+    stats = check_against_oracle(Y, oracle_on(d), "bf16", "smallm %dx%dx%d" % (M, K, N))
+    print(stats)
+
+
+def test_small_m_shape_through_tiled_path_agrees():
+    """The same small-M problem through the tiled kernels must meet the same gates."""
+    d = make_inputs(16, 1024, 1024, "bf16", seed=12)
+    Y, used = gpu_run(d, FUSED)
+    assert used == FUSED
+    check_against_oracle(Y, oracle_on(d), "bf16")
+
+
+# ------------------------------------------------------------- exact GEMM stage
+@pytest.mark.parametrize("M,K,N,dtype", [(300, 200, 520, "bf16"), (2085, 264, 4088, "bf16"),
+                                         (512, 4096, 256, "bf16"), (77, 36, 132, "f32"),
+                                         (2100, 96, 2048, "f32")])
+def test_linear_stage_exact_on_integers(M, K, N, dtype):
+    """Integer-valued inputs: every partial sum is an exact integer below 2^24, so the
+    MFMA core must reproduce the oracle's Z bit for bit (any summation order)."""
+    _announce("exact", M, K, N, dtype)
+    d = make_integer_inputs(M, K, N, dtype, seed=13)
+    Z = B.ff_debug_linear(d["X"].cuda(), d["W"].cuda(), d["b"].cuda())
+    torch.cuda.synchronize()
+    ref = oracle.fused_linear_gelu_ln(to_np32(d["X"]), to_np32(d["W"]), to_np32(d["b"]),
+                                      None, None, 1e-5, stages=True)["Z"]
+    assert np.array_equal(Z.cpu().numpy().astype(np.float64), ref)
+
+
+# ------------------------------------------------- full sizes, sampled rows
+@pytest.mark.parametrize("name", ["cfg1", "cfg2", "cfg3", "cfg4"])
+def test_benchmark_sizes_sampled_rows(name):
+    """The launch configuration the benchmark times, checked on complete sampled
+    rows (LayerNorm needs whole rows): tile-boundary rows plus seeded random rows."""
+    wl = CONFIGS[name]
+    _announce("sampled", name)
+    d = make_inputs(wl.M, wl.K, wl.N, wl.dtype, seed=0)
+    Y, used = gpu_run(d, AUTO)
+    assert used == (SMALLM if name == "cfg3" else FUSED)
+    rows = list(range(wl.M)) if wl.M <= 64 else sample_rows(wl.M, 48)
+    ref = oracle_on(d, rows=rows)
+    stats = check_against_oracle(Y[torch.tensor(rows)], ref, wl.dtype, name)
+    print(name, stats)
+    # property that holds at any size: per-row moments of (Y - beta) / gamma
+    g = d["gamma"].float().cuda()
+    bta = d["beta"].float().cuda()
+    T = (Y.float() - bta) / g
+    assert float(T.mean(dim=1).abs().max()) < 2e-2
+    assert float((T.var(dim=1, unbiased=False) - 1).abs().max()) < 2e-2
+
+
+def test_wide_rows_plain_affine_moments():
+    """gamma = 1, beta = 0 on the wide-row workload: every output row has mean 0 and
+    biased variance var/(var+eps) ~ 1, up to bf16 output rounding."""
+    wl = CONFIGS["cfg4"]
+    d = make_inputs(wl.M, wl.K, wl.N, wl.dtype, seed=0, plain_affine=True)
+    Y, used = gpu_run(d, AUTO)
+    assert used == FUSED
+    Yf = Y.float()
+    assert float(Yf.mean(dim=1).abs().max()) < 2e-3
+    assert float((Yf.var(dim=1, unbiased=False) - 1).abs().max()) < 5e-3
+    rows = sample_rows(wl.M, 16)
+    check_against_oracle(Y[torch.tensor(rows)], oracle_on(d, rows=rows), "bf16", "cfg4 plain")
+
+
+# ------------------------------------------------------------------ edge cases
+def test_optional_vectors_default_to_0_1_0():
+    d = make_inputs(200, 64, 264, "bf16", seed=14)
+    d2 = dict(d, b=None, gamma=None, beta=None)
+    Y, _ = gpu_run(d2, AUTO)
+    check_against_oracle(Y, oracle_on(d2), "bf16")
+    d3 = dict(make_inputs(16, 64, 264, "bf16", seed=14), b=None, gamma=None, beta=None)
+    Y, used = gpu_run(d3, AUTO)
+    assert used == SMALLM
+    check_against_oracle(Y, oracle_on(d3), "bf16")
+
+
+@pytest.mark.parametrize("M,variant", [(200, AUTO), (16, AUTO)])
+def test_constant_rows_give_beta(M, variant):
+    """W = 0, constant bias: G is constant along each row, so Y = beta (the
+    variance is zero; eps keeps the division finite)."""
+    d = make_inputs(M, 64, 512, "bf16", seed=15)
+    d["W"] = torch.zeros_like(d["W"])
+    d["b"] = torch.full_like(d["b"], 0.75)
+    Y, _ = gpu_run(d, variant)
+    ref = np.broadcast_to(to_np32(d["beta"]).astype(np.float64), (M, 512))
+    assert np.max(np.abs(to_np32(Y).astype(np.float64) - ref)) <= 1e-3
+
+
+def test_identity_x_transposes_w():
+    K = 256
+    d = make_inputs(K, K, 512, "f32", seed=16)
+    d["X"] = torch.eye(K, dtype=torch.float32)
+    Z = B.ff_debug_linear(d["X"].cuda(), d["W"].cuda(), d["b"].cuda())
+    want = d["W"].t().double() + d["b"].double()[None, :]
+    assert torch.equal(Z.cpu().double(), want.float().double()) or \
+        float((Z.cpu().double() - want).abs().max()) < 1e-6
+
+
+def test_bitwise_deterministic_run_to_run():
+    for (M, K, N, dt) in ((2085, 264, 4088, "bf16"), (16, 1024, 4096, "bf16"), (256, 512, 512, "f32")):
+        d = make_inputs(M, K, N, dt, seed=17)
+        dev = {k: (v.cuda() if isinstance(v, torch.Tensor) else v) for k, v in d.items()}
+        outs = []
+        for _ in range(3):
+            outs.append(B.ff_fused_linear_gelu_ln(dev["X"], dev["W"], dev["b"], dev["gamma"],
+                                                  dev["beta"], d["eps"]).clone())
+        torch.cuda.synchronize()
+        assert torch.equal(outs[0], outs[1]) and torch.equal(outs[0], outs[2])
+    B.ff_check_device()
+
+
+def test_poisoned_caller_workspace():
+    """A caller-owned workspace full of NaN bit patterns: nothing may be read before it is written."""
+    M, K, N = 600, 128, 1032
+    need = B.ff_workspace_bytes(M, K, N, B.FF_BF16)
+    assert need > 0
+    ws = torch.full((need // 4 + 64,), float("nan"), dtype=torch.float32, device="cuda")
+    B.ff_set_workspace(ws)
+    try:
+        d = make_inputs(M, K, N, "bf16", seed=18)
+        Y, _ = gpu_run(d, AUTO)
+        check_against_oracle(Y, oracle_on(d), "bf16")
+        B.ff_debug_force_variant(TWOPASS)
+        assert B.ff_workspace_bytes(M, K, N, B.FF_BF16) > need
+        B.ff_debug_force_variant(AUTO)
+        with pytest.raises(B.FFError) as e:
+            gpu_run(d, TWOPASS)           # bound workspace is too small for the fp32 G
+        assert e.value.status == 6
+    finally:
+        B.ff_debug_force_variant(AUTO)
+        B.ff_set_workspace(None)
+    Y, _ = gpu_run(d, TWOPASS)             # library-owned workspace again
+    check_against_oracle(Y, oracle_on(d), "bf16")
+
+
+def test_forced_variant_never_substitutes():
+    d = make_inputs(64, 64, 64, "bf16", seed=19)
+    with pytest.raises(B.FFError) as e:
+        gpu_run(d, SMALLM)
+    assert e.value.status == 5
+    d = make_inputs(8, 64, 64, "f32", seed=19)
+    with pytest.raises(B.FFError):
+        gpu_run(d, SMALLM)
+
+
+def test_nonzero_stream():
+    d = make_inputs(300, 128, 520, "bf16", seed=20)
+    dev = {k: (v.cuda() if isinstance(v, torch.Tensor) else v) for k, v in d.items()}
+    s = torch.cuda.Stream()
+    torch.cuda.synchronize()
+    with torch.cuda.stream(s):
+        Y = B.ff_fused_linear_gelu_ln(dev["X"], dev["W"], dev["b"], dev["gamma"], dev["beta"], d["eps"])
+    s.synchronize()
+    check_against_oracle(Y, oracle_on(d), "bf16")
