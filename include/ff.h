@@ -57,7 +57,7 @@ typedef enum { FF_F32 = 0, FF_BF16 = 1 } ff_dtype;
 typedef enum {
     FF_OK = 0,
     FF_ERR_NULL = 1,        /* a required pointer is NULL */
-    FF_ERR_SHAPE = 2,       /* M, K or N not positive, or too large */
+    FF_ERR_SHAPE = 2,       /* M, K or N not positive, or M, N > 2^30, or K > 2^21 */
     FF_ERR_DTYPE = 3,       /* dtype is neither FF_F32 nor FF_BF16 */
     FF_ERR_ALIGN = 4,       /* a pointer is not 16-byte aligned */
     FF_ERR_UNSUPPORTED = 5, /* K or N not a multiple of the 16-byte vector; or a

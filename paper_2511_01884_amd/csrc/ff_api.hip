@@ -47,7 +47,9 @@ int validate_shape(int64_t M, int64_t K, int64_t N, int dtype)
         return FF_ERR_DTYPE;
     if (M <= 0 || K <= 0 || N <= 0)
         return FF_ERR_SHAPE;
-    if (M > (int64_t)1 << 30 || K > (int64_t)1 << 30 || N > (int64_t)1 << 30)
+    // K is bounded so that 256 rows of X or W span less than 4 GiB (the kernels
+    // address a tile's rows with 32-bit byte offsets)
+    if (M > (int64_t)1 << 30 || K > (int64_t)1 << 21 || N > (int64_t)1 << 30)
         return FF_ERR_SHAPE;
     const int vec = dtype == FF_BF16 ? 8 : 4;
     if (K % vec != 0 || N % vec != 0)
@@ -332,7 +334,7 @@ const char *ff_status_string(int status)
     switch (status) {
     case FF_OK: return "FF_OK";
     case FF_ERR_NULL: return "FF_ERR_NULL: a required pointer is NULL";
-    case FF_ERR_SHAPE: return "FF_ERR_SHAPE: M, K and N must be positive and below 2^30";
+    case FF_ERR_SHAPE: return "FF_ERR_SHAPE: M, K and N must be positive, M and N at most 2^30, K at most 2^21";
     case FF_ERR_DTYPE: return "FF_ERR_DTYPE: dtype must be FF_F32 or FF_BF16";
     case FF_ERR_ALIGN: return "FF_ERR_ALIGN: pointers must be 16-byte aligned";
     case FF_ERR_UNSUPPORTED: return "FF_ERR_UNSUPPORTED: K and N must be multiples of 8 (bf16) or 4 (fp32), or the forced variant cannot run this shape";

@@ -83,10 +83,32 @@ __device__ __forceinline__ void merge_stats(float &na, float &mean_a, float &m2a
     na = n;
 }
 
-// Device-scope release / acquire around the cross-workgroup exchange of row
-// statistics: workgroups of one launch run on different XCDs with separate L2s.
-__device__ __forceinline__ void release_device() { __threadfence(); }
-__device__ __forceinline__ void acquire_device() { __threadfence(); }
+// Cross-workgroup exchange of row statistics.  Workgroups of one launch run on
+// different XCDs with separate L2 caches, so the 8-byte (mean, M2) partials are
+// written and read with device-scope atomic accesses: the store writes through to
+// the level all XCDs share, the load never takes a stale line of the local L2.
+// A full fence (L2 write-back plus invalidate) would also be correct but costs
+// tens of microseconds per launch.  Ordering: every publishing thread waits for
+// its own stores to complete (vmcnt), the workgroup meets at a barrier, and only
+// then one thread bumps the arrival counter; readers load the partials after they
+// have seen the counter reach its target.
+__device__ __forceinline__ void publish_pair(floatx2 *p, floatx2 v)
+{
+    __hip_atomic_store(reinterpret_cast<unsigned long long *>(p),
+                       __builtin_bit_cast(unsigned long long, v), __ATOMIC_RELAXED,
+                       __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ floatx2 read_pair(const floatx2 *p)
+{
+    const unsigned long long bits = __hip_atomic_load(
+        reinterpret_cast<const unsigned long long *>(p), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    return __builtin_bit_cast(floatx2, bits);
+}
+// This thread's published partials have reached the shared level.
+__device__ __forceinline__ void wait_published()
+{
+    __builtin_amdgcn_s_waitcnt(0x0f70);  // vmcnt(0)
+}
 
 __device__ __forceinline__ unsigned atomic_add_device(unsigned *p, unsigned v)
 {

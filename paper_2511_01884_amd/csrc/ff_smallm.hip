@@ -18,7 +18,7 @@ namespace {
 constexpr int kWaves = 8;
 constexpr int kThreads = 64 * kWaves;
 constexpr int kStripTiles = kSmallMStripCols / 16;  // 16-column MFMA tiles per strip
-constexpr int kUnroll = 8;                          // MFMA k-steps (32 elements) per batch
+constexpr int kUnroll = 4;                          // MFMA k-steps (32 elements) per batch
 
 __device__ __forceinline__ uintx4 load16_nt(const void *p)
 {
@@ -71,38 +71,28 @@ __global__ __launch_bounds__(kThreads) void smallm_kernel(const SmallMParams p)
             n = n < N ? n : N - 1;
             wrow[t] = W + (size_t)n * K;
         }
+        // X rows beyond M are clamped, not zeroed: they only feed output rows that
+        // are never stored, and every row's statistics are independent.
         const __bf16 *xrow[MT];
-        bool xok[MT];
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt) {
             const int m = mt * 16 + l16;
-            xok[mt] = m < M;
-            xrow[mt] = X + (size_t)(xok[mt] ? m : 0) * K;
+            xrow[mt] = X + (size_t)(m < M ? m : M - 1) * K;
         }
 
-        for (int ks0 = ks_begin; ks0 < ks_end; ks0 += kUnroll) {
-            uintx4 wf[kUnroll][kStripTiles];
-            uintx4 xf[kUnroll][MT];
+        auto load_batch = [&](int ks0, uintx4 (&wf)[kUnroll][kStripTiles], uintx4 (&xf)[kUnroll][MT]) {
 #pragma unroll
             for (int u = 0; u < kUnroll; ++u) {
                 const int k = (ks0 + u) * 32 + kg * 8;
-                const bool kok = (ks0 + u) < ks_end && k < K;
-                const int kc = kok ? k : 0;
 #pragma unroll
-                for (int mt = 0; mt < MT; ++mt) {
-                    uintx4 v = *reinterpret_cast<const uintx4 *>(xrow[mt] + kc);
-                    if (!(kok && xok[mt]))
-                        v = uintx4{0u, 0u, 0u, 0u};
-                    xf[u][mt] = v;
-                }
+                for (int mt = 0; mt < MT; ++mt)
+                    xf[u][mt] = *reinterpret_cast<const uintx4 *>(xrow[mt] + k);
 #pragma unroll
-                for (int t = 0; t < kStripTiles; ++t) {
-                    uintx4 v = load16_nt(wrow[t] + kc);
-                    if (!kok)
-                        v = uintx4{0u, 0u, 0u, 0u};
-                    wf[u][t] = v;
-                }
+                for (int t = 0; t < kStripTiles; ++t)
+                    wf[u][t] = load16_nt(wrow[t] + k);
             }
+        };
+        auto mma_batch = [&](const uintx4 (&wf)[kUnroll][kStripTiles], const uintx4 (&xf)[kUnroll][MT]) {
 #pragma unroll
             for (int u = 0; u < kUnroll; ++u)
 #pragma unroll
@@ -114,6 +104,42 @@ __global__ __launch_bounds__(kThreads) void smallm_kernel(const SmallMParams p)
                         acc[t][mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
                             __builtin_bit_cast(bf16x8, wf[u][t]),
                             __builtin_bit_cast(bf16x8, xf[u][mt]), acc[t][mt], 0, 0, 0);
+        };
+
+        // Full batches of kUnroll k-steps, software-pipelined two deep so that a
+        // batch of loads is always in flight behind the one being multiplied.
+        const int full_end = (ks_end < K / 32) ? ks_end : K / 32;  // k-steps with all 32 elements
+        const int nb = full_end > ks_begin ? (full_end - ks_begin) / kUnroll : 0;
+        uintx4 wf0[kUnroll][kStripTiles], xf0[kUnroll][MT];
+        uintx4 wf1[kUnroll][kStripTiles], xf1[kUnroll][MT];
+        if (nb > 0)
+            load_batch(ks_begin, wf0, xf0);
+        int bi = 0;
+        for (; bi + 2 <= nb; bi += 2) {
+            load_batch(ks_begin + (bi + 1) * kUnroll, wf1, xf1);
+            mma_batch(wf0, xf0);
+            if (bi + 2 < nb)
+                load_batch(ks_begin + (bi + 2) * kUnroll, wf0, xf0);
+            mma_batch(wf1, xf1);
+        }
+        if (bi < nb)
+            mma_batch(wf0, xf0);
+        // remaining k-steps one at a time; the last one may be cut by K
+        for (int ks = ks_begin + nb * kUnroll; ks < ks_end; ++ks) {
+            const int k = ks * 32 + kg * 8;
+            const unsigned keep = k < K ? 0xffffffffu : 0u;
+            const int kc = k < K ? k : 0;
+#pragma unroll
+            for (int t = 0; t < kStripTiles; ++t) {
+                uintx4 w = load16_nt(wrow[t] + kc);
+                w &= keep;
+#pragma unroll
+                for (int mt = 0; mt < MT; ++mt) {
+                    const uintx4 x = *reinterpret_cast<const uintx4 *>(xrow[mt] + kc);
+                    acc[t][mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
+                        __builtin_bit_cast(bf16x8, w), __builtin_bit_cast(bf16x8, x), acc[t][mt], 0, 0, 0);
+                }
+            }
         }
 
         // ---- sum the 8 waves' partial products in wave order ----
@@ -162,7 +188,7 @@ __global__ __launch_bounds__(kThreads) void smallm_kernel(const SmallMParams p)
                 m2 = fmaf(d, d, m2);
             }
             floatx2 o = {mean, m2};
-            p.partials[(size_t)strip * (MT * 16) + tid] = o;
+            publish_pair(p.partials + (size_t)strip * (MT * 16) + tid, o);
         }
 #pragma unroll
         for (int e = 0; e < MT; ++e) {
@@ -176,7 +202,7 @@ __global__ __launch_bounds__(kThreads) void smallm_kernel(const SmallMParams p)
     }
 
     // ---- exchange the strip statistics across the whole grid ----
-    release_device();
+    wait_published();
     __syncthreads();
     if (tid == 0) {
         atomic_add_device(p.counters, 1u);
@@ -184,7 +210,6 @@ __global__ __launch_bounds__(kThreads) void smallm_kernel(const SmallMParams p)
             atomic_store_device(p.err, 1u);
     }
     __syncthreads();
-    acquire_device();
     {
         // 32 chunks of consecutive strips per row, merged in order, then the
         // 32 chunk results merged in order by one thread per row.
@@ -196,7 +221,7 @@ __global__ __launch_bounds__(kThreads) void smallm_kernel(const SmallMParams p)
         for (int s = chunk * per; s < (chunk + 1) * per && s < p.strips; ++s) {
             const int cnt = (N - s * kSmallMStripCols < kSmallMStripCols) ? (N - s * kSmallMStripCols)
                                                                            : kSmallMStripCols;
-            const floatx2 u = p.partials[(size_t)s * (MT * 16) + row];
+            const floatx2 u = read_pair(p.partials + (size_t)s * (MT * 16) + row);
             merge_stats(na, mean_a, m2a, (float)cnt, u[0], u[1]);
         }
         // chunk counts are implied by position; pass them through LDS as (mean, M2)

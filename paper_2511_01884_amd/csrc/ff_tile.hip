@@ -1,8 +1,10 @@
 // Tiled MFMA path of the fused linear + erf-GELU + LayerNorm operator (gfx950).
 //
 // One workgroup (4 wavefronts) owns a BM x BN tile of the output and walks K in
-// 128-byte slabs.  X and W slabs go HBM -> LDS with 16-byte direct-to-LDS loads,
-// double-buffered, and are read back as MFMA fragments.  The MFMA is issued
+// 64-byte slabs.  X and W slabs go HBM -> LDS with 16-byte direct-to-LDS loads
+// into a ring of four stages (loads run three slabs ahead of the MFMAs, one
+// barrier per slab), and are read back as MFMA fragments one k-step ahead of
+// their use, so the matrix pipe does not wait on LDS latency after a barrier.  The MFMA is issued
 // "transposed" (A operand = W rows, B operand = X rows), so that a lane's 16
 // accumulator registers of a 32x32 block run along N — the LayerNorm reduction
 // axis — and the row statistics need only one cross-lane step.
@@ -27,7 +29,11 @@ namespace {
 constexpr int kWavesN = 2;
 constexpr int kWavesM = 2;
 constexpr int kThreads = 64 * kWavesN * kWavesM;
-constexpr int kRowBytes = 128;  // bytes of one tile row per K slab (8 chunks of 16 B)
+constexpr int kRowBytes = 64;   // bytes of one tile row per K slab (4 chunks of 16 B)
+constexpr int kChunksPerRow = kRowBytes / 16;
+constexpr int kStepsPerSlab = kChunksPerRow / 2;  // a k-step consumes two chunks (one per lane half)
+constexpr int kStages = 4;
+constexpr int kRowsPerDma = 1024 / kRowBytes;     // one direct-to-LDS instruction fills 1 KiB
 
 template <typename T>
 struct Mma;
@@ -63,9 +69,33 @@ __device__ __forceinline__ void wave_lds_sync()
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
-// LDS placement of 16-byte chunk `c` (0..7) of tile row `row`: chunks are XORed
-// with row bits so that the 32 rows a fragment read touches spread over all banks.
-__device__ __forceinline__ int swizzle_of_row(int row) { return (row & 7) ^ ((row >> 3) & 1); }
+// Workgroup barrier for the K loop.  Unlike __syncthreads() it carries no fence,
+// so it does not wait for outstanding global loads: direct-to-LDS loads of later
+// slabs stay in flight across it (their completion is awaited explicitly with
+// vmcnt).  It waits for this wave's own LDS reads and writes, and the barrier
+// instruction itself is a compiler-level ordering point for memory operations.
+__device__ __forceinline__ void lds_barrier()
+{
+    __builtin_amdgcn_s_waitcnt(0xc07f);  // lgkmcnt(0) only
+    __builtin_amdgcn_s_barrier();
+}
+
+// Ordering point for the instruction scheduler: the listed accumulators must have
+// been produced before it, and no memory operation moves across it.
+__device__ __forceinline__ void pin_order(floatx16 &c0) { asm volatile("" : "+a"(c0) : : "memory"); }
+__device__ __forceinline__ void pin_order(floatx16 &c0, floatx16 &c1)
+{
+    asm volatile("" : "+a"(c0), "+a"(c1) : : "memory");
+}
+
+// LDS placement of 16-byte chunk `c` (0..3) of tile row `row`: chunks are XORed
+// with row bits so that the 16 consecutive rows a fragment read touches per pass
+// (stride 64 B) spread over all 64 banks.
+__device__ __forceinline__ int swizzle_of_row(int row) { return (row >> 2) & 3; }
+
+// MFMA instructions one fragment pair costs per k-step (scheduling hints only).
+template <typename T> struct MmaCount { static constexpr int value = 1; };
+template <> struct MmaCount<float> { static constexpr int value = 4; };
 
 template <typename T, int WTN, int WTM, int MODE>
 __global__ __launch_bounds__(kThreads) void tile_kernel(const TileParams p)
@@ -77,9 +107,10 @@ __global__ __launch_bounds__(kThreads) void tile_kernel(const TileParams p)
     constexpr int kABytes = BN * kRowBytes;
     constexpr int kBBytes = BM * kRowBytes;
     constexpr int kStageBytes = kABytes + kBBytes;
-    // DMA instructions per wave per stage: each covers 8 rows (1 KiB).
-    constexpr int kDmaA = BN / 8 / (kWavesN * kWavesM);
-    constexpr int kDmaB = BM / 8 / (kWavesN * kWavesM);
+    // direct-to-LDS instructions per wave per slab
+    constexpr int kDmaA = BN / kRowsPerDma / (kWavesN * kWavesM);
+    constexpr int kDmaB = BM / kRowsPerDma / (kWavesN * kWavesM);
+    constexpr int kDmaPerSlab = kDmaA + kDmaB;
     // epilogue LDS regions (reuse the stage buffers)
     using OutT = typename std::conditional<MODE == kFused, T, float>::type;
     constexpr int kOutRowBytes = WTN * 32 * (int)sizeof(OutT);
@@ -89,7 +120,7 @@ __global__ __launch_bounds__(kThreads) void tile_kernel(const TileParams p)
     constexpr int kOffRst = kOffWst + kWavesN * BM * 8;      // BM float2
     constexpr int kOffOut = (kOffRst + BM * 8 + 1023) & ~1023;
     constexpr int kEpiBytes = kOffOut + kWavesN * kWavesM * 32 * kOutPitch;
-    constexpr int kSmemBytes = (2 * kStageBytes > kEpiBytes) ? 2 * kStageBytes : kEpiBytes;
+    constexpr int kSmemBytes = (kStages * kStageBytes > kEpiBytes) ? kStages * kStageBytes : kEpiBytes;
 
     __shared__ __attribute__((aligned(1024))) char smem[kSmemBytes];
 
@@ -106,14 +137,14 @@ __global__ __launch_bounds__(kThreads) void tile_kernel(const TileParams p)
     const bool k_ragged = (K % kSlabElems) != 0;
     const size_t row_stride = (size_t)K * sizeof(T);
 
-    // fragment read offsets (bytes inside a stage) for k-step 0; k-step s XORs (2s) << 4
+    // fragment read offsets (bytes inside a stage); k-step s reads chunk (2s + h) ^ swizzle
     const int frag_swz = swizzle_of_row(l32);
     const int a_frag_base = (wn * WTN * 32 + l32) * kRowBytes;
     const int b_frag_base = kABytes + (wm * WTM * 32 + l32) * kRowBytes;
 
-    // DMA lane geometry: lane -> (row within an 8-row group, stored chunk slot)
-    const int dma_r8 = lane >> 3;
-    const int dma_cs = lane & 7;
+    // DMA lane geometry: lane -> (row within a 16-row group, stored chunk slot)
+    const int dma_r = lane / kChunksPerRow;
+    const int dma_cs = lane % kChunksPerRow;
 
     for (int t = blockIdx.x; t < p.rounds * (int)gridDim.x; t += gridDim.x) {
         // ---- tile coordinates (XCD-aware order inside a round when enabled) ----
@@ -136,61 +167,77 @@ __global__ __launch_bounds__(kThreads) void tile_kernel(const TileParams p)
         const int m0 = rb * BM;
         const int n0 = cb * BN;
 
-        // ---- per-lane global source pointers for the DMA (slab 0) ----
-        const char *ga[kDmaA];
-        const char *gb[kDmaB];
+        // ---- per-lane byte offsets of the DMA sources, relative to the tile's first row ----
+        const char *w_tile = (const char *)p.W + (size_t)n0 * row_stride;
+        const char *x_tile = (const char *)p.X + (size_t)m0 * row_stride;
+        unsigned offa[kDmaA], offb[kDmaB];
 #pragma unroll
         for (int j = 0; j < kDmaA; ++j) {
-            const int row = wave * (BN / 4) + j * 8 + dma_r8;
+            const int row = wave * (BN / 4) + j * kRowsPerDma + dma_r;
             const int c = dma_cs ^ swizzle_of_row(row);
-            int n = n0 + row;
-            n = n < N ? n : N - 1;
-            ga[j] = (const char *)p.W + (size_t)n * row_stride + c * 16;
+            const int rr = (n0 + row < N) ? row : (N - 1 - n0);  // clamp to the last valid row
+            offa[j] = (unsigned)rr * (unsigned)row_stride + c * 16;
         }
 #pragma unroll
         for (int j = 0; j < kDmaB; ++j) {
-            const int row = wave * (BM / 4) + j * 8 + dma_r8;
+            const int row = wave * (BM / 4) + j * kRowsPerDma + dma_r;
             const int c = dma_cs ^ swizzle_of_row(row);
-            int m = m0 + row;
-            m = m < M ? m : M - 1;
-            gb[j] = (const char *)p.X + (size_t)m * row_stride + c * 16;
+            const int rr = (m0 + row < M) ? row : (M - 1 - m0);
+            offb[j] = (unsigned)rr * (unsigned)row_stride + c * 16;
         }
 
-        auto issue_slab = [&](int slab, int stage) {
+        // full slab: direct-to-LDS, nothing passes through registers.  dma_one issues
+        // the x-th of the wave's kDmaPerSlab instructions (W rows first, then X rows).
+        auto dma_one = [&](int slab, int x) {
+            const int stage = slab % kStages;
+            if (x < kDmaA) {
+                char *sa = smem + stage * kStageBytes + wave * (BN / 4) * kRowBytes;
+                const char *wk = w_tile + (size_t)slab * kRowBytes;
+                __builtin_amdgcn_global_load_lds(
+                    (const __attribute__((address_space(1))) void *)(wk + offa[x < kDmaA ? x : 0]),
+                    (__attribute__((address_space(3))) void *)(sa + x * 1024), 16, 0, 0);
+            } else {
+                const int y = x - kDmaA;
+                char *sb = smem + stage * kStageBytes + kABytes + wave * (BM / 4) * kRowBytes;
+                const char *xk = x_tile + (size_t)slab * kRowBytes;
+                __builtin_amdgcn_global_load_lds(
+                    (const __attribute__((address_space(1))) void *)(xk + offb[y >= 0 && y < kDmaB ? y : 0]),
+                    (__attribute__((address_space(3))) void *)(sb + y * 1024), 16, 0, 0);
+            }
+        };
+        auto issue_full = [&](int slab) {
+#pragma unroll
+            for (int x = 0; x < kDmaPerSlab; ++x)
+                dma_one(slab, x);
+        };
+        // any slab: the last one may be cut by K, then chunks at or beyond K are zero-filled
+        auto issue_any = [&](int slab) {
+            if (!k_ragged || slab + 1 < slabs) {
+                issue_full(slab);
+                return;
+            }
+            const int stage = slab % kStages;
             char *sa = smem + stage * kStageBytes + wave * (BN / 4) * kRowBytes;
             char *sb = smem + stage * kStageBytes + kABytes + wave * (BM / 4) * kRowBytes;
-            const size_t koff = (size_t)slab * kRowBytes;
-            if (!k_ragged || slab + 1 < slabs) {
+            const char *wk = w_tile + (size_t)slab * kRowBytes;
+            const char *xk = x_tile + (size_t)slab * kRowBytes;
 #pragma unroll
-                for (int j = 0; j < kDmaA; ++j)
-                    __builtin_amdgcn_global_load_lds(
-                        (const __attribute__((address_space(1))) void *)(ga[j] + koff),
-                        (__attribute__((address_space(3))) void *)(sa + j * 1024), 16, 0, 0);
+            for (int j = 0; j < kDmaA; ++j) {
+                const int row = wave * (BN / 4) + j * kRowsPerDma + dma_r;
+                const int c = dma_cs ^ swizzle_of_row(row);
+                const bool in = slab * kSlabElems + c * kChunkElems < K;
+                uintx4 v = *reinterpret_cast<const uintx4 *>(in ? wk + offa[j] : w_tile);
+                v &= in ? 0xffffffffu : 0u;
+                *reinterpret_cast<uintx4 *>(sa + j * 1024 + lane * 16) = v;
+            }
 #pragma unroll
-                for (int j = 0; j < kDmaB; ++j)
-                    __builtin_amdgcn_global_load_lds(
-                        (const __attribute__((address_space(1))) void *)(gb[j] + koff),
-                        (__attribute__((address_space(3))) void *)(sb + j * 1024), 16, 0, 0);
-            } else {
-                // last, partial slab: chunks at or beyond K are zero-filled
-#pragma unroll
-                for (int j = 0; j < kDmaA; ++j) {
-                    const int row = wave * (BN / 4) + j * 8 + dma_r8;
-                    const int c = dma_cs ^ swizzle_of_row(row);
-                    uintx4 v = {0u, 0u, 0u, 0u};
-                    if (slab * kSlabElems + c * kChunkElems < K)
-                        v = *reinterpret_cast<const uintx4 *>(ga[j] + koff);
-                    *reinterpret_cast<uintx4 *>(sa + j * 1024 + lane * 16) = v;
-                }
-#pragma unroll
-                for (int j = 0; j < kDmaB; ++j) {
-                    const int row = wave * (BM / 4) + j * 8 + dma_r8;
-                    const int c = dma_cs ^ swizzle_of_row(row);
-                    uintx4 v = {0u, 0u, 0u, 0u};
-                    if (slab * kSlabElems + c * kChunkElems < K)
-                        v = *reinterpret_cast<const uintx4 *>(gb[j] + koff);
-                    *reinterpret_cast<uintx4 *>(sb + j * 1024 + lane * 16) = v;
-                }
+            for (int j = 0; j < kDmaB; ++j) {
+                const int row = wave * (BM / 4) + j * kRowsPerDma + dma_r;
+                const int c = dma_cs ^ swizzle_of_row(row);
+                const bool in = slab * kSlabElems + c * kChunkElems < K;
+                uintx4 v = *reinterpret_cast<const uintx4 *>(in ? xk + offb[j] : x_tile);
+                v &= in ? 0xffffffffu : 0u;
+                *reinterpret_cast<uintx4 *>(sb + j * 1024 + lane * 16) = v;
             }
         };
 
@@ -203,34 +250,101 @@ __global__ __launch_bounds__(kThreads) void tile_kernel(const TileParams p)
                 for (int r = 0; r < 16; ++r)
                     acc[i][j][r] = 0.0f;
 
-        // ---- main loop over K slabs, two LDS stages ----
-        __syncthreads();  // previous tile's epilogue is done with the LDS
-        issue_slab(0, 0);
-        for (int slab = 0; slab < slabs; ++slab) {
-            const int stage = slab & 1;
-            __builtin_amdgcn_s_waitcnt(0);  // this wave's loads of `slab` have landed
-            __syncthreads();                // everyone's have; stage^1 is free again
-            if (slab + 1 < slabs)
-                issue_slab(slab + 1, stage ^ 1);
-            const char *sbase = smem + stage * kStageBytes;
+        uintx4 fa[2][WTN], fb[2][WTM];  // fragment registers, double-buffered by k-step
+        // x-th fragment read of (slab, k-step s): W fragments first, then X fragments
+        auto read_one = [&](int slab, int s, int x, uintx4 (&a)[WTN], uintx4 (&b)[WTM]) {
+            const char *sbase = smem + (slab % kStages) * kStageBytes;
+            const int coff = ((2 * s + h) ^ frag_swz) << 4;
+            if (x < WTN)
+                a[x < WTN ? x : 0] = *reinterpret_cast<const uintx4 *>(
+                    sbase + a_frag_base + x * 32 * kRowBytes + coff);
+            else
+                b[x >= WTN ? x - WTN : 0] = *reinterpret_cast<const uintx4 *>(
+                    sbase + b_frag_base + (x - WTN) * 32 * kRowBytes + coff);
+        };
+        auto load_frags = [&](int slab, int s, uintx4 (&a)[WTN], uintx4 (&b)[WTM]) {
 #pragma unroll
-            for (int s = 0; s < 4; ++s) {
-                const int coff = ((2 * s + h) ^ frag_swz) << 4;
-                uintx4 fa[WTN], fb[WTM];
+            for (int x = 0; x < WTN + WTM; ++x)
+                read_one(slab, s, x, a, b);
+        };
+        // the MFMAs are issued in kGroups groups of kPerGroup fragment pairs
+        constexpr int kGroups = WTN + WTM;
+        constexpr int kPerGroup = WTN * WTM / kGroups;
+        static_assert(kPerGroup * kGroups == WTN * WTM, "pairs must split evenly over the groups");
+        static_assert(kPerGroup == 1 || kPerGroup == 2, "pin_order takes one or two accumulators");
+        auto mma_group = [&](int g, const uintx4 (&a)[WTN], const uintx4 (&b)[WTM]) {
 #pragma unroll
-                for (int i = 0; i < WTN; ++i)
-                    fa[i] = *reinterpret_cast<const uintx4 *>(sbase + a_frag_base +
-                                                              i * 32 * kRowBytes + coff);
-#pragma unroll
-                for (int j = 0; j < WTM; ++j)
-                    fb[j] = *reinterpret_cast<const uintx4 *>(sbase + b_frag_base +
-                                                              j * 32 * kRowBytes + coff);
-#pragma unroll
-                for (int i = 0; i < WTN; ++i)
-#pragma unroll
-                    for (int j = 0; j < WTM; ++j)
-                        Mma<T>::step(fa[i], fb[j], acc[i][j]);
+            for (int q = 0; q < kPerGroup; ++q) {
+                const int pair = g * kPerGroup + q;
+                Mma<T>::step(a[pair / WTM], b[pair % WTM], acc[pair / WTM][pair % WTM]);
             }
+        };
+        auto pin_group = [&](int g) {
+            const int p0 = g * kPerGroup;
+            if (kPerGroup == 2)
+                pin_order(acc[p0 / WTM][p0 % WTM], acc[(p0 + 1) / WTM][(p0 + 1) % WTM]);
+            else
+                pin_order(acc[p0 / WTM][p0 % WTM]);
+        };
+        auto mma_all = [&](const uintx4 (&a)[WTN], const uintx4 (&b)[WTM]) {
+#pragma unroll
+            for (int g = 0; g < kGroups; ++g)
+                mma_group(g, a, b);
+        };
+
+        // ---- main loop over K slabs ----
+        // Invariant at the top of iteration i (after barrier B_i): slabs <= i+1 are
+        // visible in LDS to every wave, every wave has finished reading slab i-1, and
+        // the fragments of (slab i, k-step 0) are already on their way to registers.
+        static_assert(kStepsPerSlab == 2, "the loop body below is written for two k-steps per slab");
+        static_assert(kDmaPerSlab <= kGroups, "one DMA instruction per MFMA group at most");
+        __syncthreads();  // previous tile's epilogue is done with the LDS
+        for (int sl = 0; sl < 3 && sl < slabs; ++sl)
+            issue_any(sl);
+        if (slabs > 2)
+            __builtin_amdgcn_s_waitcnt(0x0f70 | (kDmaPerSlab & 15) | ((kDmaPerSlab >> 4) << 14));
+        else
+            __builtin_amdgcn_s_waitcnt(0x0f70);  // vmcnt(0)
+        lds_barrier();
+        load_frags(0, 0, fa[0], fb[0]);
+
+        // steady iterations: the slab issued (i+3) exists and is a full one.  The
+        // instruction order below is the intended issue order (one DMA and one LDS
+        // read in the shadow of each group of MFMAs); the scheduling fences keep it.
+        const int n_steady = slabs - 3 - (k_ragged ? 1 : 0);
+        int i = 0;
+        for (; i < n_steady; ++i) {
+#pragma unroll
+            for (int g = 0; g < kGroups; ++g) {
+                if (g < kDmaPerSlab)
+                    dma_one(i + 3, g);
+                read_one(i, 1, g, fa[1], fb[1]);
+                mma_group(g, fa[0], fb[0]);
+                pin_group(g);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+#pragma unroll
+            for (int g = 0; g < kGroups; ++g) {
+                mma_group(g, fa[1], fb[1]);
+                read_one(i + 1, 0, g, fa[0], fb[0]);
+                pin_group(g);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            // all but the newest slab's loads have landed; then B_{i+1}
+            __builtin_amdgcn_s_waitcnt(0x0f70 | (kDmaPerSlab & 15) | ((kDmaPerSlab >> 4) << 14));
+            lds_barrier();
+        }
+        // last (up to four) iterations: nothing, or a K-cut slab, left to issue
+        for (; i < slabs; ++i) {
+            if (i + 3 < slabs)
+                issue_any(i + 3);
+            load_frags(i, 1, fa[1], fb[1]);
+            mma_all(fa[0], fb[0]);
+            if (i + 1 < slabs)
+                load_frags(i + 1, 0, fa[0], fb[0]);
+            mma_all(fa[1], fb[1]);
+            __builtin_amdgcn_s_waitcnt(0x0f70);  // vmcnt(0)
+            lds_barrier();
         }
         __syncthreads();  // all fragment reads done: LDS becomes epilogue scratch
 
@@ -321,13 +435,16 @@ __global__ __launch_bounds__(kThreads) void tile_kernel(const TileParams p)
                     merge_stats(na, mean_a, m2a, (float)cw, u[0], u[1]);
                 }
                 floatx2 o = {mean_a, m2a};
-                p.partials[((size_t)rb * p.NT + cb) * BM + tid] = o;
+                if (MODE == kFused)
+                    publish_pair(p.partials + ((size_t)rb * p.NT + cb) * BM + tid, o);
+                else
+                    p.partials[((size_t)rb * p.NT + cb) * BM + tid] = o;
             }
         }
 
         if (MODE == kFused) {
             // exchange with the other tiles of these rows
-            release_device();
+            wait_published();
             __syncthreads();
             if (tid == 0) {
                 unsigned *arrive = p.counters + 2 * (size_t)rb;
@@ -336,12 +453,11 @@ __global__ __launch_bounds__(kThreads) void tile_kernel(const TileParams p)
                     atomic_store_device(p.err, 1u);
             }
             __syncthreads();
-            acquire_device();
             if (tid < BM) {
                 float na = 0.0f, mean_a = 0.0f, m2a = 0.0f;
                 for (int c = 0; c < p.NT; ++c) {
                     const int cnt = (N - c * BN < BN) ? (N - c * BN) : BN;
-                    const floatx2 u = p.partials[((size_t)rb * p.NT + c) * BM + tid];
+                    const floatx2 u = read_pair(p.partials + ((size_t)rb * p.NT + c) * BM + tid);
                     merge_stats(na, mean_a, m2a, (float)cnt, u[0], u[1]);
                 }
                 const float var = m2a / (float)N;
