@@ -47,24 +47,24 @@ __device__ __forceinline__ unsigned pack_bf16x2(float lo, float hi)
 // g = z * Phi(z), Phi(z) = 0.5 * erfc(-z / sqrt 2).  erfc(x), x >= 0, uses the
 // five-term rational-times-Gaussian formula of Abramowitz & Stegun 7.1.26,
 //     erfc(x) ~ (a1 t + a2 t^2 + a3 t^3 + a4 t^4 + a5 t^5) exp(-x^2),  t = 1/(1 + p x),
-// absolute error <= 1.5e-7.  Evaluating the tail directly (instead of 1 + erf)
-// keeps that absolute bound for negative z, where 1 + erf would cancel; the
-// error in g is <= 0.75e-7 * |z|.
+// absolute error <= 1.5e-7.  With q = Phi(-|z|) = 0.5 erfc(|z| / sqrt 2) evaluated
+// directly (no 1 + erf cancellation), g = max(z, 0) - |z| q for either sign of z;
+// the error in g is <= 0.75e-7 |z| plus rounding.  The 0.5 is folded into the
+// coefficients; the reciprocal and 2^x are the hardware approximations (1 ulp).
 __device__ __forceinline__ float gelu_erf(float z)
 {
     const float x = fabsf(z) * 0.70710678118654752f;
-    const float t = __frcp_rn(fmaf(0.3275911f, x, 1.0f));
-    float p = 1.061405429f;
-    p = fmaf(p, t, -1.453152027f);
-    p = fmaf(p, t, 1.421413741f);
-    p = fmaf(p, t, -0.284496736f);
-    p = fmaf(p, t, 0.254829592f);
+    const float t = __builtin_amdgcn_rcpf(fmaf(0.3275911f, x, 1.0f));
+    float p = 0.5f * 1.061405429f;
+    p = fmaf(p, t, 0.5f * -1.453152027f);
+    p = fmaf(p, t, 0.5f * 1.421413741f);
+    p = fmaf(p, t, 0.5f * -0.284496736f);
+    p = fmaf(p, t, 0.5f * 0.254829592f);
     p *= t;
     // exp(-x^2) = 2^(-z^2 * log2(e) / 2)
-    const float e = __builtin_amdgcn_exp2f(z * z * -0.72134752044448170f);
-    const float q = 0.5f * p * e;            // Phi(-|z|)
-    const float phi = z > 0.0f ? 1.0f - q : q;
-    return z * phi;
+    const float e = __builtin_amdgcn_exp2f((z * z) * -0.72134752044448170f);
+    const float q = p * e;
+    return fmaf(-fabsf(z), q, fmaxf(z, 0.0f));
 }
 
 // ---- (count, mean, M2) merge (Chan et al. pairwise update) ---------------------
@@ -124,7 +124,8 @@ __device__ __forceinline__ void atomic_store_device(unsigned *p, unsigned v)
 }
 
 // Wait (bounded) until *counter >= target.  Returns false if the bound expired.
-// One thread calls this; the rest of the workgroup waits at a barrier.
+// One thread calls this; the rest of the workgroup waits at a barrier.  The clock
+// is read only every 256 polls: reading it costs as much as a poll.
 __device__ __forceinline__ bool wait_counter(const unsigned *counter, unsigned target,
                                              long long limit_ticks)
 {
@@ -132,9 +133,11 @@ __device__ __forceinline__ bool wait_counter(const unsigned *counter, unsigned t
         return true;
     const long long t0 = wall_clock64();
     for (;;) {
-        __builtin_amdgcn_s_sleep(4);
-        if (atomic_load_device(counter) >= target)
-            return true;
+        for (int i = 0; i < 256; ++i) {
+            __builtin_amdgcn_s_sleep(1);
+            if (atomic_load_device(counter) >= target)
+                return true;
+        }
         if (wall_clock64() - t0 > limit_ticks)
             return false;
     }

@@ -1,14 +1,21 @@
 // Small-M path (M <= 32, bf16) of the fused linear + erf-GELU + LayerNorm
 // operator: a streamer, not a tiled GEMM.  The cost is reading W once, so each
-// workgroup owns a strip of 32 output columns, its 8 wavefronts split K, and
-// every wave streams its share of the strip's W rows with 16-byte loads, many
-// in flight, straight into 16x16x32 MFMA operands (M = 16 fills the MFMA's row
-// block exactly; the tiny X comes from L2).  The row statistics span all
-// workgroups, so they are exchanged as 8-byte (mean, M2) partials through
-// global memory with an arrival counter inside the same launch — a second
-// launch would cost a visible fraction of the ~17 us the stream itself takes.
-// This is the paper's bandwidth-bound diagnosis pattern (App. B.1: a kernel at
-// DRAM peak is fixed by removing passes over memory, not by more arithmetic).
+// workgroup owns a strip of 32 output columns (32 rows of W, one contiguous
+// block), its 8 wavefronts split K, and every wave streams its share with 16-byte
+// loads arranged so that eight lanes cover one whole 128-byte line of a row — the
+// pattern that reaches the same HBM rate as a linear copy.  The loaded registers
+// are MFMA operands as they are: a load instruction covers 8 rows x 64 k, which a
+// 16x16x32 MFMA sees as 16 "virtual" rows (row r with k 0..31, row r+8 with k
+// 32..63); multiplying once by X[k 0..31] and once by X[k 32..63] leaves the wanted
+// products in the lower and upper half of two accumulators, which are added when
+// the waves' partial sums are combined in LDS.  M = 16 fills the MFMA's other
+// dimension exactly; the tiny X comes from L2.
+// The row statistics span all workgroups, so they are exchanged as 8-byte
+// (mean, M2) partials through global memory with an arrival counter inside the
+// same launch — a second launch would cost a visible fraction of the ~20 us the
+// stream itself takes.  This is the paper's bandwidth-bound diagnosis pattern
+// (App. B.1: a kernel at DRAM peak is fixed by removing passes over memory, not
+// by more arithmetic).
 #include "ff_tile.hpp"
 
 namespace ff {
@@ -17,187 +24,226 @@ namespace {
 
 constexpr int kWaves = 8;
 constexpr int kThreads = 64 * kWaves;
-constexpr int kStripTiles = kSmallMStripCols / 16;  // 16-column MFMA tiles per strip
-constexpr int kUnroll = 4;                          // MFMA k-steps (32 elements) per batch
+constexpr int kRowGroups = kSmallMStripCols / 8;  // load instructions cover 8 rows of W
+constexpr int kSegElems = 64;                     // one 128-byte line of a row
+constexpr int kUnroll = 2;                        // segments per batch of loads
 
 __device__ __forceinline__ uintx4 load16_nt(const void *p)
 {
     return __builtin_nontemporal_load(reinterpret_cast<const uintx4 *>(p));
 }
 
+__device__ __forceinline__ floatx4 mfma16(const uintx4 &a, const uintx4 &b, const floatx4 &c)
+{
+    return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a),
+                                                   __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
+}
+
 // MT = number of 16-row blocks of X (1: M <= 16, 2: M <= 32).
 template <int MT>
 __global__ __launch_bounds__(kThreads) void smallm_kernel(const SmallMParams p)
 {
-    __shared__ float s_part[kWaves][kStripTiles][MT][4][64];  // per-wave accumulators
-    __shared__ float s_g[MT * 16][kSmallMStripCols];          // G of the current strip
-    __shared__ floatx2 s_chunk[32][MT * 16];                  // merged statistics per chunk
-    __shared__ floatx2 s_rst[MT * 16];                        // (mean, rstd) per row
+    // per-wave partial products, already in (row m, column) order; the row pitch of 33
+    // keeps both the scattered writes and the row-wise reads free of bank conflicts
+    __shared__ float s_part[kWaves][2][MT * 16][kSmallMStripCols + 1];
+    __shared__ floatx2 s_wave[kWaves][MT * 16];       // merged statistics per wave
+    __shared__ floatx2 s_rst[MT * 16];                // (mean, rstd) per row
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int l16 = lane & 15;
-    const int kg = lane >> 4;  // which 8-element group of a 32-element k-step
     const int M = p.M, N = p.N, K = p.K;
     const __bf16 *X = reinterpret_cast<const __bf16 *>(p.X);
     const __bf16 *W = reinterpret_cast<const __bf16 *>(p.W);
 
-    // K range of this wave, in k-steps of 32 elements
-    const int ksteps = (K + 31) / 32;
-    const int per_wave = (ksteps + kWaves - 1) / kWaves;
-    const int ks_begin = wave * per_wave;
-    const int ks_end = (ks_begin + per_wave < ksteps) ? ks_begin + per_wave : ksteps;
+    // W operand: lane -> (row of the 8-row group, 16-byte chunk of the 128-byte segment).
+    // MFMA row i = lane & 15 is physical row i & 7 with chunk (i >> 3) * 4 + (lane >> 4).
+    const int w_row = lane & 7;
+    const int w_chunk = ((lane >> 3) & 1) * 4 + (lane >> 4);
+    // X operand: lane -> (row m = lane & 15, k group lane >> 4), lower and upper k half
+    const int x_row = lane & 15;
+    const int x_kg = lane >> 4;
+
+    // K range of this wave, in 64-element segments
+    const int segs = (K + kSegElems - 1) / kSegElems;
+    const int per_wave = (segs + kWaves - 1) / kWaves;
+    const int sg_begin = wave * per_wave;
+    const int sg_end = (sg_begin + per_wave < segs) ? sg_begin + per_wave : segs;
+    const int full_end = (sg_end < K / kSegElems) ? sg_end : K / kSegElems;  // whole segments only
 
     // Final-store ownership: thread `tid` owns elements e = tid + i * 512, i < MT, of a
     // strip's [16 MT][32] block of G (row e / 32, column e % 32).
+    // Column e % 32 is the same for every i (512 % 32 == 0), so one bias / gamma / beta
+    // value per strip serves all of a thread's elements.
     float g_keep[kSmallMMaxStripsPerGroup][MT];  // my G values of each strip this group owns
+    float ga_keep[kSmallMMaxStripsPerGroup], be_keep[kSmallMMaxStripsPerGroup];
+    const int my_col = tid % kSmallMStripCols;
+
+    // X rows beyond M are clamped, not zeroed: they only feed output rows that are
+    // never stored, and every row's statistics are independent.
+    const __bf16 *xrow[MT];
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) {
+        const int m = mt * 16 + x_row;
+        xrow[mt] = X + (size_t)(m < M ? m : M - 1) * K + x_kg * 8;
+    }
 
     int owned = 0;
     for (int strip = blockIdx.x; strip < p.strips; strip += gridDim.x, ++owned) {
         const int n0 = strip * kSmallMStripCols;
-        floatx4 acc[kStripTiles][MT];
+        // this thread's column vectors, requested before the stream so that their
+        // latency hides behind it
+        const int my_n = n0 + my_col;
+        const bool my_ok = my_n < N;
+        const __bf16 *vb = reinterpret_cast<const __bf16 *>(p.b);
+        const __bf16 *vg = reinterpret_cast<const __bf16 *>(p.gamma);
+        const __bf16 *ve = reinterpret_cast<const __bf16 *>(p.beta);
+        const float my_bias = (vb && my_ok) ? load_as_float(vb + my_n) : 0.0f;
+        const float my_gamma = (vg && my_ok) ? load_as_float(vg + my_n) : 1.0f;
+        const float my_beta = (ve && my_ok) ? load_as_float(ve + my_n) : 0.0f;
 #pragma unroll
-        for (int t = 0; t < kStripTiles; ++t)
+        for (int i = 0; i < kSmallMMaxStripsPerGroup; ++i)
+            if (i == owned) {
+                ga_keep[i] = my_gamma;
+                be_keep[i] = my_beta;
+            }
+        floatx4 acc[kRowGroups][MT][2];
+#pragma unroll
+        for (int rg = 0; rg < kRowGroups; ++rg)
 #pragma unroll
             for (int mt = 0; mt < MT; ++mt)
-                acc[t][mt] = floatx4{0.0f, 0.0f, 0.0f, 0.0f};
+                acc[rg][mt][0] = acc[rg][mt][1] = floatx4{0.0f, 0.0f, 0.0f, 0.0f};
 
-        // per-lane row pointers: W rows n0 + t*16 + l16 (clamped), X rows mt*16 + l16
-        const __bf16 *wrow[kStripTiles];
+        const __bf16 *wrow[kRowGroups];
 #pragma unroll
-        for (int t = 0; t < kStripTiles; ++t) {
-            int n = n0 + t * 16 + l16;
+        for (int rg = 0; rg < kRowGroups; ++rg) {
+            int n = n0 + rg * 8 + w_row;
             n = n < N ? n : N - 1;
-            wrow[t] = W + (size_t)n * K;
-        }
-        // X rows beyond M are clamped, not zeroed: they only feed output rows that
-        // are never stored, and every row's statistics are independent.
-        const __bf16 *xrow[MT];
-#pragma unroll
-        for (int mt = 0; mt < MT; ++mt) {
-            const int m = mt * 16 + l16;
-            xrow[mt] = X + (size_t)(m < M ? m : M - 1) * K;
+            wrow[rg] = W + (size_t)n * K + w_chunk * 8;
         }
 
-        auto load_batch = [&](int ks0, uintx4 (&wf)[kUnroll][kStripTiles], uintx4 (&xf)[kUnroll][MT]) {
+        auto load_batch = [&](int sg0, uintx4 (&wf)[kUnroll][kRowGroups], uintx4 (&xf)[kUnroll][MT][2]) {
 #pragma unroll
             for (int u = 0; u < kUnroll; ++u) {
-                const int k = (ks0 + u) * 32 + kg * 8;
+                const int k = (sg0 + u) * kSegElems;
 #pragma unroll
-                for (int mt = 0; mt < MT; ++mt)
-                    xf[u][mt] = *reinterpret_cast<const uintx4 *>(xrow[mt] + k);
+                for (int mt = 0; mt < MT; ++mt) {
+                    xf[u][mt][0] = *reinterpret_cast<const uintx4 *>(xrow[mt] + k);
+                    xf[u][mt][1] = *reinterpret_cast<const uintx4 *>(xrow[mt] + k + 32);
+                }
 #pragma unroll
-                for (int t = 0; t < kStripTiles; ++t)
-                    wf[u][t] = load16_nt(wrow[t] + k);
+                for (int rg = 0; rg < kRowGroups; ++rg)
+                    wf[u][rg] = load16_nt(wrow[rg] + k);
             }
         };
-        auto mma_batch = [&](const uintx4 (&wf)[kUnroll][kStripTiles], const uintx4 (&xf)[kUnroll][MT]) {
+        auto mma_batch = [&](const uintx4 (&wf)[kUnroll][kRowGroups], const uintx4 (&xf)[kUnroll][MT][2]) {
 #pragma unroll
             for (int u = 0; u < kUnroll; ++u)
 #pragma unroll
-                for (int t = 0; t < kStripTiles; ++t)
+                for (int rg = 0; rg < kRowGroups; ++rg)
 #pragma unroll
-                    for (int mt = 0; mt < MT; ++mt)
-                        // A operand = W rows (register index runs along n),
-                        // B operand = X rows (lane index runs along m)
-                        acc[t][mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
-                            __builtin_bit_cast(bf16x8, wf[u][t]),
-                            __builtin_bit_cast(bf16x8, xf[u][mt]), acc[t][mt], 0, 0, 0);
+                    for (int mt = 0; mt < MT; ++mt) {
+                        // A operand = W (register index of the result runs along n),
+                        // B operand = X (lane index of the result runs along m)
+                        acc[rg][mt][0] = mfma16(wf[u][rg], xf[u][mt][0], acc[rg][mt][0]);
+                        acc[rg][mt][1] = mfma16(wf[u][rg], xf[u][mt][1], acc[rg][mt][1]);
+                    }
         };
 
-        // Full batches of kUnroll k-steps, software-pipelined two deep so that a
+        // Whole segments in batches of kUnroll, software-pipelined two deep so that a
         // batch of loads is always in flight behind the one being multiplied.
-        const int full_end = (ks_end < K / 32) ? ks_end : K / 32;  // k-steps with all 32 elements
-        const int nb = full_end > ks_begin ? (full_end - ks_begin) / kUnroll : 0;
-        uintx4 wf0[kUnroll][kStripTiles], xf0[kUnroll][MT];
-        uintx4 wf1[kUnroll][kStripTiles], xf1[kUnroll][MT];
+        const int nb = full_end > sg_begin ? (full_end - sg_begin) / kUnroll : 0;
+        uintx4 wf0[kUnroll][kRowGroups], xf0[kUnroll][MT][2];
+        uintx4 wf1[kUnroll][kRowGroups], xf1[kUnroll][MT][2];
         if (nb > 0)
-            load_batch(ks_begin, wf0, xf0);
+            load_batch(sg_begin, wf0, xf0);
         int bi = 0;
         for (; bi + 2 <= nb; bi += 2) {
-            load_batch(ks_begin + (bi + 1) * kUnroll, wf1, xf1);
+            load_batch(sg_begin + (bi + 1) * kUnroll, wf1, xf1);
             mma_batch(wf0, xf0);
             if (bi + 2 < nb)
-                load_batch(ks_begin + (bi + 2) * kUnroll, wf0, xf0);
+                load_batch(sg_begin + (bi + 2) * kUnroll, wf0, xf0);
             mma_batch(wf1, xf1);
         }
         if (bi < nb)
             mma_batch(wf0, xf0);
-        // remaining k-steps one at a time; the last one may be cut by K
-        for (int ks = ks_begin + nb * kUnroll; ks < ks_end; ++ks) {
-            const int k = ks * 32 + kg * 8;
-            const unsigned keep = k < K ? 0xffffffffu : 0u;
-            const int kc = k < K ? k : 0;
+        // remaining segments one at a time; the last one may be cut by K (K % 8 == 0,
+        // so 16-byte chunks are whole): chunks of W at or beyond K are zeroed
+        for (int sg = sg_begin + nb * kUnroll; sg < sg_end; ++sg) {
+            const int k = sg * kSegElems;
+            const bool w_in = k + w_chunk * 8 < K;
+            const unsigned keep = w_in ? 0xffffffffu : 0u;
+            uintx4 x[MT][2];
 #pragma unroll
-            for (int t = 0; t < kStripTiles; ++t) {
-                uintx4 w = load16_nt(wrow[t] + kc);
+            for (int mt = 0; mt < MT; ++mt) {
+                x[mt][0] = *reinterpret_cast<const uintx4 *>(xrow[mt] + (k + x_kg * 8 < K ? k : 0));
+                x[mt][1] = *reinterpret_cast<const uintx4 *>(xrow[mt] + (k + 32 + x_kg * 8 < K ? k + 32 : 0));
+            }
+#pragma unroll
+            for (int rg = 0; rg < kRowGroups; ++rg) {
+                uintx4 w = load16_nt(wrow[rg] + (w_in ? k : 0));
                 w &= keep;
 #pragma unroll
                 for (int mt = 0; mt < MT; ++mt) {
-                    const uintx4 x = *reinterpret_cast<const uintx4 *>(xrow[mt] + kc);
-                    acc[t][mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
-                        __builtin_bit_cast(bf16x8, w), __builtin_bit_cast(bf16x8, x), acc[t][mt], 0, 0, 0);
+                    acc[rg][mt][0] = mfma16(w, x[mt][0], acc[rg][mt][0]);
+                    acc[rg][mt][1] = mfma16(w, x[mt][1], acc[rg][mt][1]);
                 }
             }
         }
 
         // ---- sum the 8 waves' partial products in wave order ----
         __syncthreads();  // s_part / s_g of the previous strip are no longer read
+        // Result layout of a 16x16 MFMA: lane (j = lane & 15, g = lane >> 4), register t
+        // holds result row 4 g + t, column j.  Rows 0..7 of the lower-k accumulator and
+        // rows 8..15 of the upper-k accumulator are the wanted products of W row
+        // (4 g + t) & 7, so lane groups 0,1 store the former and 2,3 the latter.
+        {
+            const int j = lane & 15, g = lane >> 4;
+            const int hf = g >> 1;
 #pragma unroll
-        for (int t = 0; t < kStripTiles; ++t)
+            for (int rg = 0; rg < kRowGroups; ++rg)
 #pragma unroll
-            for (int mt = 0; mt < MT; ++mt)
+                for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
-                for (int r = 0; r < 4; ++r)
-                    s_part[wave][t][mt][r][lane] = acc[t][mt][r];
-        __syncthreads();
-        // kStripTiles * MT * 4 * 64 outputs over 512 threads
-        constexpr int kOutputs = kStripTiles * MT * 4 * 64;
-        for (int o = tid; o < kOutputs; o += kThreads) {
-            const int ol = o & 63;
-            const int r = (o >> 6) & 3;
-            const int mt = (o >> 8) % MT;
-            const int t = (o >> 8) / MT;
-            float z = 0.0f;
-#pragma unroll
-            for (int w = 0; w < kWaves; ++w)
-                z += s_part[w][t][mt][r][ol];
-            // element (m, n): lane index runs along m, register along n
-            const int m = mt * 16 + (ol & 15);
-            const int nl = t * 16 + 4 * (ol >> 4) + r;
-            const int n = n0 + nl;
-            float g = 0.0f;
-            if (n < N) {
-                const float bias = p.b ? load_as_float(reinterpret_cast<const __bf16 *>(p.b) + n) : 0.0f;
-                g = gelu_erf(z + bias);
-            }
-            s_g[m][nl] = g;
+                    for (int t = 0; t < 4; ++t) {
+                        const float v = hf ? acc[rg][mt][1][t] : acc[rg][mt][0][t];
+                        s_part[wave][hf][mt * 16 + j][rg * 8 + 4 * (g & 1) + t] = v;
+                    }
         }
         __syncthreads();
-        // ---- per-row (mean, M2) of the strip; keep my G value in a register ----
         const int nvalid = (N - n0 < kSmallMStripCols) ? (N - n0) : kSmallMStripCols;
-        if (tid < MT * 16) {
-            float s = 0.0f;
-            for (int c = 0; c < nvalid; ++c)
-                s += s_g[tid][c];
-            const float mean = s / (float)nvalid;
-            float m2 = 0.0f;
-            for (int c = 0; c < nvalid; ++c) {
-                const float d = s_g[tid][c] - mean;
-                m2 = fmaf(d, d, m2);
-            }
-            floatx2 o = {mean, m2};
-            publish_pair(p.partials + (size_t)strip * (MT * 16) + tid, o);
-        }
 #pragma unroll
         for (int e = 0; e < MT; ++e) {
             const int el = tid + e * kThreads;
-            const float gv = s_g[el / kSmallMStripCols][el % kSmallMStripCols];
+            const int m = el / kSmallMStripCols;
+            const int nl = my_col;
+            float z = 0.0f;
+#pragma unroll
+            for (int w = 0; w < kWaves; ++w) {
+                z += s_part[w][0][m][nl];
+                z += s_part[w][1][m][nl];
+            }
+            const float g = my_ok ? gelu_erf(z + my_bias) : 0.0f;
 #pragma unroll
             for (int i = 0; i < kSmallMMaxStripsPerGroup; ++i)
                 if (i == owned)
-                    g_keep[i][e] = gv;
+                    g_keep[i][e] = g;
+            // per-row (mean, M2) of the strip: the 32 columns of a row sit in one half
+            // of a wave, reduced with a fixed butterfly (every lane ends with the sums)
+            float sum = g;
+#pragma unroll
+            for (int off = 16; off >= 1; off >>= 1)
+                sum += __shfl_xor(sum, off);
+            const float mean = sum / (float)nvalid;
+            const float d = my_ok ? g - mean : 0.0f;
+            float m2 = d * d;
+#pragma unroll
+            for (int off = 16; off >= 1; off >>= 1)
+                m2 += __shfl_xor(m2, off);
+            if (nl == 0) {
+                floatx2 o = {mean, m2};
+                publish_pair(p.partials + (size_t)strip * (MT * 16) + m, o);
+            }
         }
     }
 
@@ -211,37 +257,62 @@ __global__ __launch_bounds__(kThreads) void smallm_kernel(const SmallMParams p)
     }
     __syncthreads();
     {
-        // 32 chunks of consecutive strips per row, merged in order, then the
-        // 32 chunk results merged in order by one thread per row.
-        const int row = tid % (MT * 16);
-        const int chunk = tid / (MT * 16);  // 0 .. 512/(16 MT) - 1
-        constexpr int kChunks = kThreads / (MT * 16);
+        // Every workgroup merges all strips' partials itself, in strip order: thread ->
+        // (row, chunk of consecutive strips); chunks of a wave are then folded with
+        // directed shuffles (earlier strips on the left), the waves' results through
+        // LDS.  Plain loads: the lines were written through by their single owner
+        // before the counter could reach its target, and no cache of this XCD can
+        // hold an older copy within this launch; workgroups of one XCD share them
+        // in its L2 instead of all hitting the same lines in memory.
+        constexpr int kRows = MT * 16;
+        constexpr int kChunks = kThreads / kRows;       // chunks per workgroup
+        constexpr int kChunksPerWave = 64 / kRows;      // 4 (MT = 1) or 2 (MT = 2)
+        const int row = tid % kRows;
+        const int chunk = tid / kRows;
         const int per = (p.strips + kChunks - 1) / kChunks;
+        auto cols_of = [&](int first, int last) {       // columns covered by strips [first, last)
+            const int a = first * kSmallMStripCols < N ? first * kSmallMStripCols : N;
+            const int b = last * kSmallMStripCols < N ? last * kSmallMStripCols : N;
+            return (float)(b - a);
+        };
+        const int s_begin = chunk * per < p.strips ? chunk * per : p.strips;
+        const int s_end = (chunk + 1) * per < p.strips ? (chunk + 1) * per : p.strips;
         float na = 0.0f, mean_a = 0.0f, m2a = 0.0f;
-        for (int s = chunk * per; s < (chunk + 1) * per && s < p.strips; ++s) {
-            const int cnt = (N - s * kSmallMStripCols < kSmallMStripCols) ? (N - s * kSmallMStripCols)
-                                                                           : kSmallMStripCols;
-            const floatx2 u = read_pair(p.partials + (size_t)s * (MT * 16) + row);
-            merge_stats(na, mean_a, m2a, (float)cnt, u[0], u[1]);
+        for (int s0 = s_begin; s0 < s_end; s0 += 8) {
+            floatx2 u[8];  // issue the loads together, then merge in order
+#pragma unroll
+            for (int j = 0; j < 8; ++j)
+                if (s0 + j < s_end)
+                    u[j] = p.partials[(size_t)(s0 + j) * kRows + row];
+#pragma unroll
+            for (int j = 0; j < 8; ++j)
+                if (s0 + j < s_end)
+                    merge_stats(na, mean_a, m2a, cols_of(s0 + j, s0 + j + 1), u[j][0], u[j][1]);
         }
-        // chunk counts are implied by position; pass them through LDS as (mean, M2)
-        // and recompute the count when merging
-        if (chunk < 32) {
+        // fold the wave's chunks: lane takes the later chunk from lane + kRows * step
+#pragma unroll
+        for (int step = 1; step < kChunksPerWave; step <<= 1) {
+            const float nb = __shfl_down(na, kRows * step);
+            const float mb = __shfl_down(mean_a, kRows * step);
+            const float qb = __shfl_down(m2a, kRows * step);
+            merge_stats(na, mean_a, m2a, nb, mb, qb);
+        }
+        if (lane < kRows) {
             floatx2 o = {mean_a, m2a};
-            s_chunk[chunk][row] = o;
+            s_wave[wave][row] = o;
         }
         __syncthreads();
-        if (tid < MT * 16) {
-            float nb_total = 0.0f, mean_t = 0.0f, m2_t = 0.0f;
-            for (int c = 0; c < kChunks; ++c) {
-                int first = c * per;
-                int last = (c + 1) * per < p.strips ? (c + 1) * per : p.strips;
-                if (first >= last)
-                    break;
-                int cols_first = first * kSmallMStripCols;
-                int cols_last = last * kSmallMStripCols < N ? last * kSmallMStripCols : N;
-                const floatx2 u = s_chunk[c][tid];
-                merge_stats(nb_total, mean_t, m2_t, (float)(cols_last - cols_first), u[0], u[1]);
+        if (tid < kRows) {
+            floatx2 u[kWaves];
+#pragma unroll
+            for (int w = 0; w < kWaves; ++w)
+                u[w] = s_wave[w][tid];
+            float nt = 0.0f, mean_t = 0.0f, m2_t = 0.0f;
+#pragma unroll
+            for (int w = 0; w < kWaves; ++w) {
+                const int first = w * kChunksPerWave * per;
+                const int last = (w + 1) * kChunksPerWave * per;
+                merge_stats(nt, mean_t, m2_t, cols_of(first, last), u[w][0], u[w][1]);
             }
             floatx2 o = {mean_t, 1.0f / sqrtf(m2_t / (float)N + p.eps)};
             s_rst[tid] = o;
@@ -258,6 +329,13 @@ __global__ __launch_bounds__(kThreads) void smallm_kernel(const SmallMParams p)
     // ---- normalise and store ----
     owned = 0;
     for (int strip = blockIdx.x; strip < p.strips; strip += gridDim.x, ++owned) {
+        float ga = 1.0f, be = 0.0f;
+#pragma unroll
+        for (int i = 0; i < kSmallMMaxStripsPerGroup; ++i)
+            if (i == owned) {
+                ga = ga_keep[i];
+                be = be_keep[i];
+            }
 #pragma unroll
         for (int e = 0; e < MT; ++e) {
             float gv = 0.0f;
@@ -267,11 +345,9 @@ __global__ __launch_bounds__(kThreads) void smallm_kernel(const SmallMParams p)
                     gv = g_keep[i][e];
             const int el = tid + e * kThreads;
             const int m = el / kSmallMStripCols;
-            const int n = strip * kSmallMStripCols + el % kSmallMStripCols;
+            const int n = strip * kSmallMStripCols + my_col;
             if (m < M && n < N) {
                 const floatx2 ms = s_rst[m];
-                const float ga = p.gamma ? load_as_float(reinterpret_cast<const __bf16 *>(p.gamma) + n) : 1.0f;
-                const float be = p.beta ? load_as_float(reinterpret_cast<const __bf16 *>(p.beta) + n) : 0.0f;
                 const float y = fmaf((gv - ms[0]) * ms[1], ga, be);
                 const float y_other = __shfl_xor(y, 1);
                 // even lanes store two adjacent bf16 values (N is a multiple of 8)

@@ -1,10 +1,11 @@
 // Tiled MFMA path of the fused linear + erf-GELU + LayerNorm operator (gfx950).
 //
 // One workgroup (4 wavefronts) owns a BM x BN tile of the output and walks K in
-// 64-byte slabs.  X and W slabs go HBM -> LDS with 16-byte direct-to-LDS loads
-// into a ring of four stages (loads run three slabs ahead of the MFMAs, one
-// barrier per slab), and are read back as MFMA fragments one k-step ahead of
-// their use, so the matrix pipe does not wait on LDS latency after a barrier.  The MFMA is issued
+// 128-byte slabs (whole cache lines: one L2 request per line).  X and W slabs go
+// HBM -> LDS with 16-byte direct-to-LDS loads into two stages; the loads of the
+// next slab are issued in the shadow of the MFMAs, the single barrier per slab
+// sits before the last k-step, and MFMA fragments are read one k-step ahead of
+// their use, so the matrix pipe does not wait on LDS latency after the barrier.  The MFMA is issued
 // "transposed" (A operand = W rows, B operand = X rows), so that a lane's 16
 // accumulator registers of a 32x32 block run along N — the LayerNorm reduction
 // axis — and the row statistics need only one cross-lane step.
@@ -29,10 +30,10 @@ namespace {
 constexpr int kWavesN = 2;
 constexpr int kWavesM = 2;
 constexpr int kThreads = 64 * kWavesN * kWavesM;
-constexpr int kRowBytes = 64;   // bytes of one tile row per K slab (4 chunks of 16 B)
+constexpr int kRowBytes = 128;  // bytes of one tile row per K slab (8 chunks of 16 B)
 constexpr int kChunksPerRow = kRowBytes / 16;
 constexpr int kStepsPerSlab = kChunksPerRow / 2;  // a k-step consumes two chunks (one per lane half)
-constexpr int kStages = 4;
+constexpr int kStages = 2;
 constexpr int kRowsPerDma = 1024 / kRowBytes;     // one direct-to-LDS instruction fills 1 KiB
 
 template <typename T>
@@ -88,16 +89,18 @@ __device__ __forceinline__ void pin_order(floatx16 &c0, floatx16 &c1)
     asm volatile("" : "+a"(c0), "+a"(c1) : : "memory");
 }
 
-// LDS placement of 16-byte chunk `c` (0..3) of tile row `row`: chunks are XORed
-// with row bits so that the 16 consecutive rows a fragment read touches per pass
-// (stride 64 B) spread over all 64 banks.
-__device__ __forceinline__ int swizzle_of_row(int row) { return (row >> 2) & 3; }
+// LDS placement of 16-byte chunk `c` (0..7) of tile row `row`: chunks are XORed
+// with row bits so that the consecutive rows a fragment read touches per pass
+// (stride 128 B) spread over all banks, for 8-lane and for 16-lane passes.
+__device__ __forceinline__ int swizzle_of_row(int row) { return (row & 7) ^ ((row >> 3) & 1); }
 
 // MFMA instructions one fragment pair costs per k-step (scheduling hints only).
 template <typename T> struct MmaCount { static constexpr int value = 1; };
 template <> struct MmaCount<float> { static constexpr int value = 4; };
 
-template <typename T, int WTN, int WTM, int MODE>
+// RAGGED_N: N is not a multiple of the tile width, so the last tile of each row
+// masks the columns at or beyond N in the statistics (chosen on the host).
+template <typename T, int WTN, int WTM, int MODE, bool RAGGED_N>
 __global__ __launch_bounds__(kThreads) void tile_kernel(const TileParams p)
 {
     constexpr int BN = kWavesN * WTN * 32;
@@ -205,39 +208,33 @@ __global__ __launch_bounds__(kThreads) void tile_kernel(const TileParams p)
                     (__attribute__((address_space(3))) void *)(sb + y * 1024), 16, 0, 0);
             }
         };
-        auto issue_full = [&](int slab) {
-#pragma unroll
-            for (int x = 0; x < kDmaPerSlab; ++x)
-                dma_one(slab, x);
-        };
-        // any slab: the last one may be cut by K, then chunks at or beyond K are zero-filled
-        auto issue_any = [&](int slab) {
-            if (!k_ragged || slab + 1 < slabs) {
-                issue_full(slab);
-                return;
-            }
+        // K-cut (last) slab: through registers, chunks at or beyond K are zero-filled
+        auto issue_cut = [&](int slab, int half) {
             const int stage = slab % kStages;
-            char *sa = smem + stage * kStageBytes + wave * (BN / 4) * kRowBytes;
-            char *sb = smem + stage * kStageBytes + kABytes + wave * (BM / 4) * kRowBytes;
-            const char *wk = w_tile + (size_t)slab * kRowBytes;
-            const char *xk = x_tile + (size_t)slab * kRowBytes;
+            if (half == 0) {
+                char *sa = smem + stage * kStageBytes + wave * (BN / 4) * kRowBytes;
+                const char *wk = w_tile + (size_t)slab * kRowBytes;
 #pragma unroll
-            for (int j = 0; j < kDmaA; ++j) {
-                const int row = wave * (BN / 4) + j * kRowsPerDma + dma_r;
-                const int c = dma_cs ^ swizzle_of_row(row);
-                const bool in = slab * kSlabElems + c * kChunkElems < K;
-                uintx4 v = *reinterpret_cast<const uintx4 *>(in ? wk + offa[j] : w_tile);
-                v &= in ? 0xffffffffu : 0u;
-                *reinterpret_cast<uintx4 *>(sa + j * 1024 + lane * 16) = v;
-            }
+                for (int j = 0; j < kDmaA; ++j) {
+                    const int row = wave * (BN / 4) + j * kRowsPerDma + dma_r;
+                    const int c = dma_cs ^ swizzle_of_row(row);
+                    const bool in = slab * kSlabElems + c * kChunkElems < K;
+                    uintx4 v = *reinterpret_cast<const uintx4 *>(in ? wk + offa[j] : w_tile);
+                    v &= in ? 0xffffffffu : 0u;
+                    *reinterpret_cast<uintx4 *>(sa + j * 1024 + lane * 16) = v;
+                }
+            } else {
+                char *sb = smem + stage * kStageBytes + kABytes + wave * (BM / 4) * kRowBytes;
+                const char *xk = x_tile + (size_t)slab * kRowBytes;
 #pragma unroll
-            for (int j = 0; j < kDmaB; ++j) {
-                const int row = wave * (BM / 4) + j * kRowsPerDma + dma_r;
-                const int c = dma_cs ^ swizzle_of_row(row);
-                const bool in = slab * kSlabElems + c * kChunkElems < K;
-                uintx4 v = *reinterpret_cast<const uintx4 *>(in ? xk + offb[j] : x_tile);
-                v &= in ? 0xffffffffu : 0u;
-                *reinterpret_cast<uintx4 *>(sb + j * 1024 + lane * 16) = v;
+                for (int j = 0; j < kDmaB; ++j) {
+                    const int row = wave * (BM / 4) + j * kRowsPerDma + dma_r;
+                    const int c = dma_cs ^ swizzle_of_row(row);
+                    const bool in = slab * kSlabElems + c * kChunkElems < K;
+                    uintx4 v = *reinterpret_cast<const uintx4 *>(in ? xk + offb[j] : x_tile);
+                    v &= in ? 0xffffffffu : 0u;
+                    *reinterpret_cast<uintx4 *>(sb + j * 1024 + lane * 16) = v;
+                }
             }
         };
 
@@ -293,58 +290,93 @@ __global__ __launch_bounds__(kThreads) void tile_kernel(const TileParams p)
         };
 
         // ---- main loop over K slabs ----
-        // Invariant at the top of iteration i (after barrier B_i): slabs <= i+1 are
-        // visible in LDS to every wave, every wave has finished reading slab i-1, and
-        // the fragments of (slab i, k-step 0) are already on their way to registers.
-        static_assert(kStepsPerSlab == 2, "the loop body below is written for two k-steps per slab");
-        static_assert(kDmaPerSlab <= kGroups, "one DMA instruction per MFMA group at most");
+        // Per slab: four k-steps, each one group-interleaved stream of MFMAs with one
+        // LDS fragment read (for the next k-step) and at most one DMA instruction in
+        // the shadow of each MFMA group.  The W half of slab i+1 is issued during
+        // k-step 3 of slab i-1... concretely, iteration i issues the X half of slab
+        // i+1 in k-step 0 and the W half of slab i+2 in k-step 3; the barrier before
+        // k-step 3 is the point where slab i+1 has landed for everyone and everyone
+        // has finished reading slab i (its stage is then refilled).
+        static_assert(kStepsPerSlab == 4 && kStages == 2, "loop body written for 4 k-steps, 2 stages");
+        static_assert(kDmaA <= kGroups && kDmaB <= kGroups, "one DMA instruction per MFMA group at most");
+        auto dma_half_any = [&](int slab, int half) {
+            // half 0: W rows (x in [0, kDmaA)), half 1: X rows; K-cut slabs go through registers
+            if (!k_ragged || slab + 1 < slabs) {
+#pragma unroll
+                for (int x = 0; x < (half == 0 ? kDmaA : kDmaB); ++x)
+                    dma_one(slab, half == 0 ? x : kDmaA + x);
+            } else {
+                issue_cut(slab, half);
+            }
+        };
         __syncthreads();  // previous tile's epilogue is done with the LDS
-        for (int sl = 0; sl < 3 && sl < slabs; ++sl)
-            issue_any(sl);
-        if (slabs > 2)
-            __builtin_amdgcn_s_waitcnt(0x0f70 | (kDmaPerSlab & 15) | ((kDmaPerSlab >> 4) << 14));
+        dma_half_any(0, 0);
+        dma_half_any(0, 1);
+        if (slabs > 1)
+            dma_half_any(1, 0);
+        if (slabs > 1 && !(k_ragged && slabs == 2))
+            __builtin_amdgcn_s_waitcnt(0x0f70 | (kDmaA & 15) | ((kDmaA >> 4) << 14));  // slab 0 landed
         else
             __builtin_amdgcn_s_waitcnt(0x0f70);  // vmcnt(0)
         lds_barrier();
         load_frags(0, 0, fa[0], fb[0]);
 
-        // steady iterations: the slab issued (i+3) exists and is a full one.  The
-        // instruction order below is the intended issue order (one DMA and one LDS
-        // read in the shadow of each group of MFMAs); the scheduling fences keep it.
-        const int n_steady = slabs - 3 - (k_ragged ? 1 : 0);
+        // steady iterations: slab i+1 and slab i+2 exist and are full ones
+        const int n_steady = slabs - 2 - (k_ragged ? 1 : 0);
         int i = 0;
         for (; i < n_steady; ++i) {
 #pragma unroll
-            for (int g = 0; g < kGroups; ++g) {
-                if (g < kDmaPerSlab)
-                    dma_one(i + 3, g);
+            for (int g = 0; g < kGroups; ++g) {  // k-step 0
+                if (g < kDmaB)
+                    dma_one(i + 1, kDmaA + g);
                 read_one(i, 1, g, fa[1], fb[1]);
                 mma_group(g, fa[0], fb[0]);
                 pin_group(g);
                 __builtin_amdgcn_sched_barrier(0);
             }
 #pragma unroll
-            for (int g = 0; g < kGroups; ++g) {
+            for (int g = 0; g < kGroups; ++g) {  // k-step 1
+                mma_group(g, fa[1], fb[1]);
+                read_one(i, 2, g, fa[0], fb[0]);
+                pin_group(g);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+#pragma unroll
+            for (int g = 0; g < kGroups; ++g) {  // k-step 2
+                mma_group(g, fa[0], fb[0]);
+                read_one(i, 3, g, fa[1], fb[1]);
+                pin_group(g);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            __builtin_amdgcn_s_waitcnt(0x0f70);  // vmcnt(0): slab i+1 has landed
+            lds_barrier();
+#pragma unroll
+            for (int g = 0; g < kGroups; ++g) {  // k-step 3
+                if (g < kDmaA)
+                    dma_one(i + 2, g);
                 mma_group(g, fa[1], fb[1]);
                 read_one(i + 1, 0, g, fa[0], fb[0]);
                 pin_group(g);
                 __builtin_amdgcn_sched_barrier(0);
             }
-            // all but the newest slab's loads have landed; then B_{i+1}
-            __builtin_amdgcn_s_waitcnt(0x0f70 | (kDmaPerSlab & 15) | ((kDmaPerSlab >> 4) << 14));
-            lds_barrier();
         }
-        // last (up to four) iterations: nothing, or a K-cut slab, left to issue
+        // last iterations: slab i+1 or i+2 is missing or cut by K
         for (; i < slabs; ++i) {
-            if (i + 3 < slabs)
-                issue_any(i + 3);
+            if (i + 1 < slabs)
+                dma_half_any(i + 1, 1);
             load_frags(i, 1, fa[1], fb[1]);
             mma_all(fa[0], fb[0]);
+            load_frags(i, 2, fa[0], fb[0]);
+            mma_all(fa[1], fb[1]);
+            load_frags(i, 3, fa[1], fb[1]);
+            mma_all(fa[0], fb[0]);
+            __builtin_amdgcn_s_waitcnt(0x0f70);  // vmcnt(0)
+            lds_barrier();
+            if (i + 2 < slabs)
+                dma_half_any(i + 2, 0);
             if (i + 1 < slabs)
                 load_frags(i + 1, 0, fa[0], fb[0]);
             mma_all(fa[1], fb[1]);
-            __builtin_amdgcn_s_waitcnt(0x0f70);  // vmcnt(0)
-            lds_barrier();
         }
         __syncthreads();  // all fragment reads done: LDS becomes epilogue scratch
 
@@ -367,60 +399,91 @@ __global__ __launch_bounds__(kThreads) void tile_kernel(const TileParams p)
 
         const int ncol_wave = wn * WTN * 32;            // wave's first column inside the tile
         const int nvalid_tile = (N - n0 < BN) ? (N - n0) : BN;
-        const bool ragged_n = nvalid_tile < BN;
 
-        // bias + GELU, in place in the accumulators
+        // bias + GELU in place in the accumulators, and per-row (count, mean, M2) of
+        // the tile.  A lane holds 16 WTN values of each of its WTM rows; their sums are
+        // taken about the lane's first value (a shift that keeps sum-of-squares
+        // cancellation harmless), merged with the other lane half, then across waves.
+        {
+            constexpr bool kRagged = RAGGED_N;
+            int cnt_own = WTN * 16, cnt_other = WTN * 16;
+            if (kRagged) {
+                cnt_own = cnt_other = 0;
 #pragma unroll
-        for (int i = 0; i < WTN; ++i)
+                for (int i = 0; i < WTN; ++i)
 #pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                const int cl = ncol_wave + i * 32 + q * 8 + h * 4;
-                const floatx4 bb = *reinterpret_cast<const floatx4 *>(s_b + cl);
+                    for (int q = 0; q < 4; ++q)
 #pragma unroll
-                for (int j = 0; j < WTM; ++j)
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) {
-                        const float z = acc[i][j][q * 4 + e] + bb[e];
-                        float g = (MODE == kLinearOnly) ? z : gelu_erf(z);
-                        if (MODE != kLinearOnly && ragged_n && cl + e >= nvalid_tile)
-                            g = 0.0f;
-                        acc[i][j][q * 4 + e] = g;
-                    }
+                        for (int e = 0; e < 4; ++e) {
+                            const int c0 = ncol_wave + i * 32 + q * 8 + e;
+                            cnt_own += (c0 + h * 4 < nvalid_tile) ? 1 : 0;
+                            cnt_other += (c0 + (h ^ 1) * 4 < nvalid_tile) ? 1 : 0;
+                        }
             }
-
-        if (MODE != kLinearOnly) {
-            // per-row (mean, M2) over this wave's columns, then over the tile
             int cntw_i = nvalid_tile - ncol_wave;
             cntw_i = cntw_i < 0 ? 0 : (cntw_i > WTN * 32 ? WTN * 32 : cntw_i);
-            const float cntw = (float)cntw_i;
+            float shift[WTM], s1[WTM], s2[WTM];
 #pragma unroll
-            for (int j = 0; j < WTM; ++j) {
-                float s = 0.0f;
+            for (int j = 0; j < WTM; ++j)
+                shift[j] = s1[j] = s2[j] = 0.0f;
 #pragma unroll
-                for (int i = 0; i < WTN; ++i)
+            for (int i = 0; i < WTN; ++i)
 #pragma unroll
-                    for (int r = 0; r < 16; ++r)
-                        s += acc[i][j][r];
-                s += __shfl_xor(s, 32);
-                const float mean = cntw_i > 0 ? s / cntw : 0.0f;
-                float m2 = 0.0f;
+                for (int q = 0; q < 4; ++q) {
+                    const int cl = ncol_wave + i * 32 + q * 8 + h * 4;
+                    const floatx4 bb = *reinterpret_cast<const floatx4 *>(s_b + cl);
 #pragma unroll
-                for (int i = 0; i < WTN; ++i)
+                    for (int j = 0; j < WTM; ++j)
 #pragma unroll
-                    for (int r = 0; r < 16; ++r) {
-                        float d = acc[i][j][r] - mean;
-                        if (ragged_n) {
-                            const int cl = ncol_wave + i * 32 + (r >> 2) * 8 + h * 4 + (r & 3);
-                            d = cl < nvalid_tile ? d : 0.0f;
+                        for (int e = 0; e < 4; ++e) {
+                            const float z = acc[i][j][q * 4 + e] + bb[e];
+                            if (MODE == kLinearOnly) {
+                                acc[i][j][q * 4 + e] = z;
+                                continue;
+                            }
+                            float g = gelu_erf(z);
+                            if (i == 0 && q == 0 && e == 0)
+                                shift[j] = g;  // column ncol_wave + 4h: valid whenever the lane has any
+                            float d = g - shift[j];
+                            if (kRagged && cl + e >= nvalid_tile) {
+                                g = 0.0f;
+                                d = 0.0f;
+                            }
+                            acc[i][j][q * 4 + e] = g;
+                            s1[j] += d;
+                            s2[j] = fmaf(d, d, s2[j]);
                         }
-                        m2 = fmaf(d, d, m2);
+                    // keep the register footprint of this unrolled epilogue small: one
+                    // (i, q) group of 16 values at a time
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+            if (MODE != kLinearOnly) {
+#pragma unroll
+                for (int j = 0; j < WTM; ++j) {
+                    // lane statistics -> merged with the other half-wave (lower half first)
+                    const float n_own = (float)cnt_own, n_oth = (float)cnt_other;
+                    const float inv_own = cnt_own > 0 ? 1.0f / n_own : 0.0f;
+                    float mean_own = fmaf(s1[j], inv_own, shift[j]);
+                    float m2_own = fmaxf(s2[j] - s1[j] * s1[j] * inv_own, 0.0f);
+                    if (kRagged && cnt_own == 0)
+                        mean_own = 0.0f;
+                    const float mean_oth = __shfl_xor(mean_own, 32);
+                    const float m2_oth = __shfl_xor(m2_own, 32);
+                    float na = h == 0 ? n_own : n_oth;
+                    float mean_a = h == 0 ? mean_own : mean_oth;
+                    float m2a = h == 0 ? m2_own : m2_oth;
+                    merge_stats(na, mean_a, m2a, h == 0 ? n_oth : n_own,
+                                h == 0 ? mean_oth : mean_own, h == 0 ? m2_oth : m2_own);
+                    if (h == 0) {
+                        floatx2 v = {mean_a, m2a};
+                        s_wst[wn * BM + wm * WTM * 32 + j * 32 + l32] = v;
                     }
-                m2 += __shfl_xor(m2, 32);
-                if (h == 0) {
-                    floatx2 v = {mean, m2};
-                    s_wst[wn * BM + wm * WTM * 32 + j * 32 + l32] = v;
                 }
             }
+            (void)cntw_i;
+        }
+
+        if (MODE != kLinearOnly) {
             __syncthreads();
             if (tid < BM) {
                 int c0 = nvalid_tile < WTN * 32 ? nvalid_tile : WTN * 32;
@@ -454,11 +517,25 @@ __global__ __launch_bounds__(kThreads) void tile_kernel(const TileParams p)
             }
             __syncthreads();
             if (tid < BM) {
+                // Plain loads: each line was written through by its single owner before
+                // the counter could reach its target, and no cache of this XCD can hold
+                // an older copy within this launch.  Loads are issued 16 at a time, the
+                // merge runs in tile order.
                 float na = 0.0f, mean_a = 0.0f, m2a = 0.0f;
-                for (int c = 0; c < p.NT; ++c) {
-                    const int cnt = (N - c * BN < BN) ? (N - c * BN) : BN;
-                    const floatx2 u = read_pair(p.partials + ((size_t)rb * p.NT + c) * BM + tid);
-                    merge_stats(na, mean_a, m2a, (float)cnt, u[0], u[1]);
+                for (int c0 = 0; c0 < p.NT; c0 += 16) {
+                    floatx2 u[16];
+#pragma unroll
+                    for (int j = 0; j < 16; ++j) {
+                        const int c = c0 + j < p.NT ? c0 + j : p.NT - 1;  // unconditional loads
+                        u[j] = p.partials[((size_t)rb * p.NT + c) * BM + tid];
+                    }
+#pragma unroll
+                    for (int j = 0; j < 16; ++j)
+                        if (c0 + j < p.NT) {
+                            const int c = c0 + j;
+                            const int cnt = (N - c * BN < BN) ? (N - c * BN) : BN;
+                            merge_stats(na, mean_a, m2a, (float)cnt, u[j][0], u[j][1]);
+                        }
                 }
                 const float var = m2a / (float)N;
                 floatx2 o = {mean_a, 1.0f / sqrtf(var + p.eps)};
@@ -480,11 +557,11 @@ __global__ __launch_bounds__(kThreads) void tile_kernel(const TileParams p)
                                           : reinterpret_cast<OutT *>(p.F);
 #pragma unroll
         for (int j = 0; j < WTM; ++j) {
-            float mu = 0.0f, rstd = 1.0f;
+            float rstd = 1.0f, shift = 0.0f;  // y = (g * rstd + shift) * gamma + beta
             if (MODE == kFused) {
                 const floatx2 ms = s_rst[wm * WTM * 32 + j * 32 + l32];
-                mu = ms[0];
                 rstd = ms[1];
+                shift = -ms[0] * ms[1];
             }
 #pragma unroll
             for (int i = 0; i < WTN; ++i)
@@ -497,7 +574,7 @@ __global__ __launch_bounds__(kThreads) void tile_kernel(const TileParams p)
                         const floatx4 be4 = *reinterpret_cast<const floatx4 *>(s_be + ncol_wave + cw);
 #pragma unroll
                         for (int e = 0; e < 4; ++e)
-                            y[e] = fmaf((acc[i][j][q * 4 + e] - mu) * rstd, ga4[e], be4[e]);
+                            y[e] = fmaf(fmaf(acc[i][j][q * 4 + e], rstd, shift), ga4[e], be4[e]);
                     } else {
 #pragma unroll
                         for (int e = 0; e < 4; ++e)
@@ -588,7 +665,11 @@ __global__ __launch_bounds__(256) void finalize_kernel(const FinalizeParams p)
 template <typename T, int WT, int MODE>
 hipError_t launch_tile(const TileParams &p, int grid, hipStream_t stream)
 {
-    hipLaunchKernelGGL((tile_kernel<T, WT, WT, MODE>), dim3(grid), dim3(kThreads), 0, stream, p);
+    constexpr int BN = kWavesN * WT * 32;
+    if (p.N % BN != 0)
+        hipLaunchKernelGGL((tile_kernel<T, WT, WT, MODE, true>), dim3(grid), dim3(kThreads), 0, stream, p);
+    else
+        hipLaunchKernelGGL((tile_kernel<T, WT, WT, MODE, false>), dim3(grid), dim3(kThreads), 0, stream, p);
     return hipGetLastError();
 }
 
