@@ -210,6 +210,12 @@ __global__ __launch_bounds__(kThreads) void tile_kernel(const TileParams p)
         };
         // K-cut (last) slab: through registers, chunks at or beyond K are zero-filled
         auto issue_cut = [&](int slab, int half) {
+            // lane geometry re-derived through an opaque move: this rarely taken path
+            // must not have its masks precomputed (and spilled) at kernel entry
+            int lane_c;
+            asm volatile("v_mov_b32 %0, %1" : "=v"(lane_c) : "v"(lane));
+            const int dma_r = lane_c / kChunksPerRow;
+            const int dma_cs = lane_c % kChunksPerRow;
             const int stage = slab % kStages;
             if (half == 0) {
                 char *sa = smem + stage * kStageBytes + wave * (BN / 4) * kRowBytes;
@@ -221,7 +227,7 @@ __global__ __launch_bounds__(kThreads) void tile_kernel(const TileParams p)
                     const bool in = slab * kSlabElems + c * kChunkElems < K;
                     uintx4 v = *reinterpret_cast<const uintx4 *>(in ? wk + offa[j] : w_tile);
                     v &= in ? 0xffffffffu : 0u;
-                    *reinterpret_cast<uintx4 *>(sa + j * 1024 + lane * 16) = v;
+                    *reinterpret_cast<uintx4 *>(sa + j * 1024 + lane_c * 16) = v;
                 }
             } else {
                 char *sb = smem + stage * kStageBytes + kABytes + wave * (BM / 4) * kRowBytes;
@@ -233,7 +239,7 @@ __global__ __launch_bounds__(kThreads) void tile_kernel(const TileParams p)
                     const bool in = slab * kSlabElems + c * kChunkElems < K;
                     uintx4 v = *reinterpret_cast<const uintx4 *>(in ? xk + offb[j] : x_tile);
                     v &= in ? 0xffffffffu : 0u;
-                    *reinterpret_cast<uintx4 *>(sb + j * 1024 + lane * 16) = v;
+                    *reinterpret_cast<uintx4 *>(sb + j * 1024 + lane_c * 16) = v;
                 }
             }
         };
@@ -381,6 +387,16 @@ __global__ __launch_bounds__(kThreads) void tile_kernel(const TileParams p)
         __syncthreads();  // all fragment reads done: LDS becomes epilogue scratch
 
         // ---- epilogue ----
+        // The thread index is re-read through an opaque move so that the epilogue's many
+        // lane-dependent addresses are computed here, once per tile, instead of being
+        // hoisted out of the tile loop and carried (spilled) across the main loop.
+        int tid_e;
+        asm volatile("v_mov_b32 %0, %1" : "=v"(tid_e) : "v"(threadIdx.x));
+        {
+        const int tid = tid_e;
+        const int lane = tid & 63;
+        const int h = lane >> 5;
+        const int l32 = lane & 31;
         float *s_b = reinterpret_cast<float *>(smem + kOffPrm);
         float *s_g = s_b + BN;
         float *s_be = s_g + BN;
@@ -427,36 +443,39 @@ __global__ __launch_bounds__(kThreads) void tile_kernel(const TileParams p)
             for (int j = 0; j < WTM; ++j)
                 shift[j] = s1[j] = s2[j] = 0.0f;
 #pragma unroll
-            for (int i = 0; i < WTN; ++i)
+            for (int i = 0; i < WTN; ++i) {
+                floatx4 bb[4];  // bias of this lane's 16 columns of block row i
 #pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    const int cl = ncol_wave + i * 32 + q * 8 + h * 4;
-                    const floatx4 bb = *reinterpret_cast<const floatx4 *>(s_b + cl);
+                for (int q = 0; q < 4; ++q)
+                    bb[q] = *reinterpret_cast<const floatx4 *>(s_b + ncol_wave + i * 32 + q * 8 + h * 4);
 #pragma unroll
-                    for (int j = 0; j < WTM; ++j)
+                for (int j = 0; j < WTM; ++j) {
+                    // one 32x32 block at a time: read its 16 registers, write back 16 G values
+                    floatx16 v = acc[i][j];
 #pragma unroll
-                        for (int e = 0; e < 4; ++e) {
-                            const float z = acc[i][j][q * 4 + e] + bb[e];
-                            if (MODE == kLinearOnly) {
-                                acc[i][j][q * 4 + e] = z;
-                                continue;
-                            }
-                            float g = gelu_erf(z);
-                            if (i == 0 && q == 0 && e == 0)
-                                shift[j] = g;  // column ncol_wave + 4h: valid whenever the lane has any
-                            float d = g - shift[j];
-                            if (kRagged && cl + e >= nvalid_tile) {
-                                g = 0.0f;
-                                d = 0.0f;
-                            }
-                            acc[i][j][q * 4 + e] = g;
-                            s1[j] += d;
-                            s2[j] = fmaf(d, d, s2[j]);
+                    for (int r = 0; r < 16; ++r) {
+                        const float z = v[r] + bb[r >> 2][r & 3];
+                        if (MODE == kLinearOnly) {
+                            v[r] = z;
+                            continue;
                         }
-                    // keep the register footprint of this unrolled epilogue small: one
-                    // (i, q) group of 16 values at a time
+                        float g = gelu_erf(z);
+                        if (i == 0 && r == 0)
+                            shift[j] = g;  // column ncol_wave + 4h: valid whenever the lane has any
+                        float d = g - shift[j];
+                        if (kRagged && ncol_wave + i * 32 + (r >> 2) * 8 + h * 4 + (r & 3) >= nvalid_tile) {
+                            g = 0.0f;
+                            d = 0.0f;
+                        }
+                        v[r] = g;
+                        s1[j] += d;
+                        s2[j] = fmaf(d, d, s2[j]);
+                    }
+                    acc[i][j] = v;
+                    pin_order(acc[i][j]);  // G goes back to the accumulator registers
                     __builtin_amdgcn_sched_barrier(0);
                 }
+            }
             if (MODE != kLinearOnly) {
 #pragma unroll
                 for (int j = 0; j < WTM; ++j) {
@@ -606,6 +625,7 @@ __global__ __launch_bounds__(kThreads) void tile_kernel(const TileParams p)
             }
             wave_lds_sync();
         }
+        }  // epilogue scope
     }
 }
 
