@@ -103,6 +103,7 @@ template <> struct MmaCount<float> { static constexpr int value = 4; };
 template <typename T, int WTN, int WTM, int MODE, bool RAGGED_N>
 __global__ __launch_bounds__(kThreads) void tile_kernel(const TileParams p)
 {
+#if defined(__HIP_DEVICE_COMPILE__)  // the body uses device-only types (buffer descriptors)
     constexpr int BN = kWavesN * WTN * 32;
     constexpr int BM = kWavesM * WTM * 32;
     constexpr int kChunkElems = 16 / (int)sizeof(T);
@@ -191,21 +192,27 @@ __global__ __launch_bounds__(kThreads) void tile_kernel(const TileParams p)
 
         // full slab: direct-to-LDS, nothing passes through registers.  dma_one issues
         // the x-th of the wave's kDmaPerSlab instructions (W rows first, then X rows).
+        // Buffer descriptors over the tile's rows: the per-lane 32-bit byte offset is
+        // the loop-invariant part of a load's address, the slab offset rides in a scalar
+        // register, so a DMA instruction costs no vector ALU work.  All addresses are
+        // clamped in-bounds above; the descriptors do not rely on range checking.
+        const __amdgpu_buffer_rsrc_t w_rsrc =
+            __builtin_amdgcn_make_buffer_rsrc(const_cast<char *>(w_tile), 0, 0xffffffffu, 0x00020000);
+        const __amdgpu_buffer_rsrc_t x_rsrc =
+            __builtin_amdgcn_make_buffer_rsrc(const_cast<char *>(x_tile), 0, 0xffffffffu, 0x00020000);
         auto dma_one = [&](int slab, int x) {
             const int stage = slab % kStages;
             if (x < kDmaA) {
                 char *sa = smem + stage * kStageBytes + wave * (BN / 4) * kRowBytes;
-                const char *wk = w_tile + (size_t)slab * kRowBytes;
-                __builtin_amdgcn_global_load_lds(
-                    (const __attribute__((address_space(1))) void *)(wk + offa[x < kDmaA ? x : 0]),
-                    (__attribute__((address_space(3))) void *)(sa + x * 1024), 16, 0, 0);
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(
+                    w_rsrc, (__attribute__((address_space(3))) void *)(sa + x * 1024), 16,
+                    offa[x < kDmaA ? x : 0], slab * kRowBytes, 0, 0);
             } else {
                 const int y = x - kDmaA;
                 char *sb = smem + stage * kStageBytes + kABytes + wave * (BM / 4) * kRowBytes;
-                const char *xk = x_tile + (size_t)slab * kRowBytes;
-                __builtin_amdgcn_global_load_lds(
-                    (const __attribute__((address_space(1))) void *)(xk + offb[y >= 0 && y < kDmaB ? y : 0]),
-                    (__attribute__((address_space(3))) void *)(sb + y * 1024), 16, 0, 0);
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(
+                    x_rsrc, (__attribute__((address_space(3))) void *)(sb + y * 1024), 16,
+                    offb[y >= 0 && y < kDmaB ? y : 0], slab * kRowBytes, 0, 0);
             }
         };
         // K-cut (last) slab: through registers, chunks at or beyond K are zero-filled
@@ -627,6 +634,9 @@ __global__ __launch_bounds__(kThreads) void tile_kernel(const TileParams p)
         }
         }  // epilogue scope
     }
+#else
+    (void)p;
+#endif
 }
 
 // Second kernel of the two-pass variant: one workgroup per row.  Merges the
