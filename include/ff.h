@@ -144,6 +144,12 @@ int ff_debug_force_variant(int variant);
  * rows before it gives up and flags FF_ERR_DEVICE (default 2,000,000). */
 int ff_debug_set_wait_limit_us(int64_t microseconds);
 
+/* Make later launches wait for `count` arrivals more than will ever come (0 restores
+ * normal operation).  With a short wait limit this forces every cross-tile wait to
+ * expire: the kernels still run to completion, flag FF_ERR_DEVICE, and write
+ * unspecified output.  Exists so that the failure path can be tested from the host. */
+int ff_debug_expect_extra_arrivals(int count);
+
 #ifdef __cplusplus
 }
 #endif

@@ -19,7 +19,7 @@ FF_VARIANT_AUTO, FF_VARIANT_TILED_FUSED, FF_VARIANT_TILED_TWOPASS, FF_VARIANT_SM
 EXPORTS = [
     "ff_fused_linear_gelu_ln", "ff_workspace_bytes", "ff_set_workspace", "ff_check_device",
     "ff_status_string", "ff_version", "ff_last_variant", "ff_debug_linear",
-    "ff_debug_force_variant", "ff_debug_set_wait_limit_us",
+    "ff_debug_force_variant", "ff_debug_set_wait_limit_us", "ff_debug_expect_extra_arrivals",
 ]
 
 _lib = None
@@ -59,6 +59,8 @@ def load() -> ctypes.CDLL:
         lib.ff_debug_force_variant.argtypes = [ci]
         lib.ff_debug_set_wait_limit_us.restype = ci
         lib.ff_debug_set_wait_limit_us.argtypes = [i64]
+        lib.ff_debug_expect_extra_arrivals.restype = ci
+        lib.ff_debug_expect_extra_arrivals.argtypes = [ci]
         _lib = lib
     return _lib
 
@@ -126,6 +128,12 @@ def ff_debug_force_variant(variant: int) -> None:
 
 def ff_debug_set_wait_limit_us(us: int) -> None:
     rc = load().ff_debug_set_wait_limit_us(int(us))
+    if rc != FF_OK:
+        raise FFError(rc)
+
+
+def ff_debug_expect_extra_arrivals(count: int) -> None:
+    rc = load().ff_debug_expect_extra_arrivals(int(count))
     if rc != FF_OK:
         raise FFError(rc)
 

@@ -26,6 +26,7 @@ std::mutex g_mutex;
 DeviceState g_dev[kMaxDevices];
 int g_forced_variant = FF_VARIANT_AUTO;
 long long g_wait_limit_us = 2000000;
+int g_extra_arrivals = 0;
 thread_local int t_last_variant = 0;
 
 struct Plan {
@@ -219,6 +220,7 @@ int run(const void *X, const void *W, const void *b, const void *gamma, const vo
         p.eps = eps;
         p.M = (int)M; p.K = (int)K; p.N = (int)N;
         p.strips = pl.strips;
+        p.extra_arrivals = g_extra_arrivals;
         p.wait_ticks = wait_ticks;
         if (launch_smallm_kernel(pl.mt, p, pl.grid, stream) != hipSuccess)
             return FF_ERR_LAUNCH;
@@ -235,6 +237,7 @@ int run(const void *X, const void *W, const void *b, const void *gamma, const vo
     p.eps = eps;
     p.M = (int)M; p.K = (int)K; p.N = (int)N;
     p.NT = pl.NT; p.RB = pl.RB; p.rounds = pl.rounds; p.swz_sc = pl.swz_sc;
+    p.extra_arrivals = g_extra_arrivals;
     p.wait_ticks = wait_ticks;
     const int mode = linear_only ? kLinearOnly
                                  : (pl.variant == FF_VARIANT_TILED_FUSED ? kFused : kTwoPass);
@@ -355,6 +358,15 @@ int ff_debug_force_variant(int variant)
         return FF_ERR_UNSUPPORTED;
     std::lock_guard<std::mutex> lock(g_mutex);
     g_forced_variant = variant;
+    return FF_OK;
+}
+
+int ff_debug_expect_extra_arrivals(int count)
+{
+    if (count < 0 || count > 1024)
+        return FF_ERR_SHAPE;
+    std::lock_guard<std::mutex> lock(g_mutex);
+    g_extra_arrivals = count;
     return FF_OK;
 }
 

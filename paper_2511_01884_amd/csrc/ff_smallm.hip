@@ -252,7 +252,7 @@ __global__ __launch_bounds__(kThreads) void smallm_kernel(const SmallMParams p)
     __syncthreads();
     if (tid == 0) {
         atomic_add_device(p.counters, 1u);
-        if (!wait_counter(p.counters, gridDim.x, p.wait_ticks))
+        if (!wait_counter(p.counters, gridDim.x + (unsigned)p.extra_arrivals, p.wait_ticks))
             atomic_store_device(p.err, 1u);
     }
     __syncthreads();

@@ -538,7 +538,7 @@ __global__ __launch_bounds__(kThreads) void tile_kernel(const TileParams p)
             if (tid == 0) {
                 unsigned *arrive = p.counters + 2 * (size_t)rb;
                 atomic_add_device(arrive, 1u);
-                if (!wait_counter(arrive, (unsigned)p.NT, p.wait_ticks))
+                if (!wait_counter(arrive, (unsigned)(p.NT + p.extra_arrivals), p.wait_ticks))
                     atomic_store_device(p.err, 1u);
             }
             __syncthreads();

@@ -25,6 +25,7 @@ struct TileParams {
     int RB;              // row-blocks
     int rounds;          // ceil(RB * NT / grid)
     int swz_sc;          // XCD-aware order: super-block width in tiles, 0 = plain order
+    int extra_arrivals;  // test hook: added to the arrival target (non-zero makes waits expire)
     long long wait_ticks;
 };
 
@@ -47,6 +48,7 @@ struct SmallMParams {
     float eps;
     int M, K, N;
     int strips;          // N / 32 rounded up
+    int extra_arrivals;  // test hook: added to the arrival target (non-zero makes waits expire)
     long long wait_ticks;
 };
 

@@ -211,3 +211,66 @@ def test_nonzero_stream():
         Y = B.ff_fused_linear_gelu_ln(dev["X"], dev["W"], dev["b"], dev["gamma"], dev["beta"], d["eps"])
     s.synchronize()
     check_against_oracle(Y, oracle_on(d), "bf16")
+
+
+# ------------------------------------------------------- failure path and graphs
+@pytest.mark.parametrize("M,K,N", [(600, 128, 1032), (16, 256, 2048)])
+def test_expired_wait_is_reported_not_hung(M, K, N):
+    """Forced from the host: the kernels wait for one arrival more than will ever
+    come, with a 3 ms limit.  They must still finish, flag FF_ERR_DEVICE once, and
+    the next ordinary call must be correct again."""
+    d = make_inputs(M, K, N, "bf16", seed=21)
+    dev = {k: (v.cuda() if isinstance(v, torch.Tensor) else v) for k, v in d.items()}
+    B.ff_debug_set_wait_limit_us(3000)
+    B.ff_debug_expect_extra_arrivals(1)
+    try:
+        B.ff_fused_linear_gelu_ln(dev["X"], dev["W"], dev["b"], dev["gamma"], dev["beta"], d["eps"])
+        with pytest.raises(B.FFError) as e:
+            B.ff_check_device()
+        assert e.value.status == 8
+    finally:
+        B.ff_debug_expect_extra_arrivals(0)
+        B.ff_debug_set_wait_limit_us(2000000)
+    B.ff_check_device()                      # state was cleared by the failed check
+    Y, _ = gpu_run(d, AUTO)
+    check_against_oracle(Y, oracle_on(d), "bf16")
+
+
+@pytest.mark.parametrize("M,K,N", [(2085, 264, 4088), (16, 1024, 4096)])
+def test_graph_replay_matches_eager(M, K, N):
+    """The call is capturable (no allocation, no memset, counters re-arm themselves):
+    every replay, with fresh inputs copied in between, equals the eager result bit for bit."""
+    d = make_inputs(M, K, N, "bf16", seed=22)
+    dev = {k: (v.cuda() if isinstance(v, torch.Tensor) else v) for k, v in d.items()}
+    Y_static = torch.empty((M, N), dtype=torch.bfloat16, device="cuda")
+    args = (dev["X"], dev["W"], dev["b"], dev["gamma"], dev["beta"], d["eps"])
+    B.ff_fused_linear_gelu_ln(*args, Y=Y_static)          # warm-up: workspace exists and is clean
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    s = torch.cuda.Stream()
+    with torch.cuda.stream(s):
+        with torch.cuda.graph(g, stream=s):
+            B.ff_fused_linear_gelu_ln(*args, Y=Y_static)
+    torch.cuda.synchronize()
+    for rep in range(4):
+        fresh = make_inputs(M, K, N, "bf16", seed=100 + rep)
+        dev["X"].copy_(fresh["X"].cuda())
+        dev["W"].copy_(fresh["W"].cuda())
+        torch.cuda.synchronize()
+        Y_eager = B.ff_fused_linear_gelu_ln(*args).clone()
+        torch.cuda.synchronize()
+        Y_static.zero_()
+        g.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(Y_static, Y_eager), "replay %d differs from eager" % rep
+    B.ff_check_device()
+    ref_in = dict(d, X=dev["X"].cpu(), W=dev["W"].cpu())
+    check_against_oracle(Y_static, oracle_on(ref_in), "bf16")
+
+
+def test_workspace_grows_between_shapes():
+    """Library-owned workspace: a larger shape after a smaller one reallocates and still works."""
+    for (M, K, N) in ((64, 64, 64), (1500, 128, 3080), (300, 64, 520)):
+        d = make_inputs(M, K, N, "bf16", seed=23)
+        Y, _ = gpu_run(d, TWOPASS)
+        check_against_oracle(Y, oracle_on(d), "bf16")
