@@ -12,6 +12,7 @@ from .oracle import (  # noqa: F401
     gelu,
     layernorm_row,
     linear_row,
+    linear_sub_rowmean_gelu_residual,
     num_threads,
     round_bf16,
 )

@@ -28,7 +28,10 @@
  * erf; GELU(z) - GELU(-z) = z; LayerNorm mean/variance closed forms; scale and
  * shift behaviour of LayerNorm; constant rows; hand-expanded tiny GEMMs with
  * non-square shapes; integer-valued exact GEMMs; X = I; an independent
- * float64 library composition.  No function here is unpinned.
+ * float64 library composition.  The second chain at the end of this file is
+ * pinned by the algebraic collapse of its row mean to one dot product (evaluated
+ * independently in the test), a hand-expanded case, special cases and a library
+ * composition.  No function here is unpinned.
  *
  * Build: gcc -O2 -fno-fast-math -ffp-contract=off -fopenmp -shared -fPIC
  */
@@ -183,4 +186,60 @@ void oracle_round_bf16(const double *in, int64_t n, double *out)
             y = x > 0 ? INFINITY : -INFINITY;
         out[i] = y;
     }
+}
+
+/*
+ * Second fused chain (the paper's fused-epilogue case study, App. B.1:
+ * Linear -> subtract -> row-mean -> GELU -> residual add):
+ *
+ *     Out[m][k] = X[m][k] + GELU( mean_n( b[n] + sum_k X[m][k] W[n][k] - s[n] ) )
+ *
+ * Written out the long way, exactly as the chain is stated: the full linear
+ * layer row, the subtraction, the mean over the N outputs, GELU of that one
+ * number, and the broadcast add to the original row.  (That the mean of a
+ * linear layer collapses to a single dot product is a property the GPU path
+ * exploits and the tests check; the oracle does not use it.)
+ *   X [M,K], W [N,K], b [N] or NULL (0), s [N] or NULL (0); rows as above.
+ *   Out [R,K] fp64; rowval [R] (the GELU value per row) optional.
+ */
+int oracle_linear_sub_rowmean_gelu_residual(const float *X, const float *W, const float *b,
+                                            const float *s, int64_t M, int64_t K, int64_t N,
+                                            const int64_t *rows, int64_t n_rows,
+                                            double *Out, double *rowval)
+{
+    if (!X || !W || !Out || M < 0 || K <= 0 || N <= 0)
+        return -1;
+    const int64_t R = rows ? n_rows : M;
+    if (rows)
+        for (int64_t r = 0; r < R; ++r)
+            if (rows[r] < 0 || rows[r] >= M)
+                return -1;
+    int failed = 0;
+#pragma omp parallel
+    {
+        double *z = (double *)malloc((size_t)N * sizeof(double));
+        if (!z) {
+#pragma omp atomic write
+            failed = 1;
+        }
+#pragma omp barrier
+        if (!failed) {
+#pragma omp for schedule(dynamic, 1)
+            for (int64_t r = 0; r < R; ++r) {
+                const int64_t m = rows ? rows[r] : r;
+                const float *x = X + (size_t)m * (size_t)K;
+                oracle_linear_row(x, W, b, K, N, z);
+                double acc = 0.0;
+                for (int64_t n = 0; n < N; ++n)
+                    acc += z[n] - (s ? (double)s[n] : 0.0);
+                const double g = oracle_gelu(acc / (double)N);
+                for (int64_t k = 0; k < K; ++k)
+                    Out[(size_t)r * (size_t)K + k] = (double)x[k] + g;
+                if (rowval)
+                    rowval[r] = g;
+            }
+        }
+        free(z);
+    }
+    return failed ? -1 : 0;
 }

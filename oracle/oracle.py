@@ -47,6 +47,8 @@ def _bind(path: str):
         fp, fp, fp, fp, fp, ctypes.c_float, i64, i64, i64, ip, i64, dp, dp, dp, dp, dp]
     lib.oracle_round_bf16.restype = None
     lib.oracle_round_bf16.argtypes = [dp, i64, dp]
+    lib.oracle_linear_sub_rowmean_gelu_residual.restype = ctypes.c_int
+    lib.oracle_linear_sub_rowmean_gelu_residual.argtypes = [fp, fp, fp, fp, i64, i64, i64, ip, i64, dp, dp]
     return lib
 
 
@@ -146,6 +148,33 @@ class Oracle:
         return Y
 
 
+    def linear_sub_rowmean_gelu_residual(self, X, W, b=None, s=None,
+                                         rows: Optional[Sequence[int]] = None, with_rowval: bool = False):
+        """Out (float64, [R,K]) = X + GELU(mean_n(X W^T + b - s)), for all or the listed rows."""
+        X = _f32(X)
+        W = _f32(W)
+        M, K = X.shape
+        N, K2 = W.shape
+        if K2 != K:
+            raise ValueError("X is [M,K], W must be [N,K]")
+        b = _f32(b, (N,))
+        s = _f32(s, (N,))
+        if rows is not None:
+            rows_a = np.ascontiguousarray(rows, dtype=np.int64)
+            R = int(rows_a.shape[0])
+        else:
+            rows_a = None
+            R = M
+        Out = np.empty((R, K), dtype=np.float64)
+        rv = np.empty(R, dtype=np.float64)
+        rc = self._lib.oracle_linear_sub_rowmean_gelu_residual(
+            _ptr(X, ctypes.c_float), _ptr(W, ctypes.c_float), _ptr(b, ctypes.c_float),
+            _ptr(s, ctypes.c_float), M, K, N, _ptr(rows_a, ctypes.c_int64), R,
+            _ptr(Out, ctypes.c_double), _ptr(rv, ctypes.c_double))
+        if rc != 0:
+            raise RuntimeError("oracle_linear_sub_rowmean_gelu_residual failed (rc=%d)" % rc)
+        return (Out, rv) if with_rowval else Out
+
     def round_bf16(self, a) -> np.ndarray:
         """Nearest bfloat16 value (ties to even) of each fp64 element, as float64."""
         a = np.ascontiguousarray(a, dtype=np.float64)
@@ -183,6 +212,10 @@ def layernorm_row(g, gamma=None, beta=None, eps: float = 0.0):
 def fused_linear_gelu_ln(X, W, b=None, gamma=None, beta=None, eps: float = 1e-5,
                          rows=None, stages: bool = False):
     return _get().fused_linear_gelu_ln(X, W, b, gamma, beta, eps, rows, stages)
+
+
+def linear_sub_rowmean_gelu_residual(X, W, b=None, s=None, rows=None, with_rowval: bool = False):
+    return _get().linear_sub_rowmean_gelu_residual(X, W, b, s, rows, with_rowval)
 
 
 def round_bf16(a):

@@ -269,3 +269,62 @@ ALL_PINS = [
     pin_gelu_moments,
     pin_round_bf16,
 ]
+
+
+# ---------------------------------------------- second chain (row-mean epilogue)
+def pin_rowmean_chain_collapse(orc):
+    """The mean over n of a linear layer is one dot product: mean_n(x.W[n] + b[n] - s[n])
+    = x . mean_n(W[n]) + mean(b - s).  Evaluated here with float64 library sums and the
+    series GELU, independently of the oracle's long-way loops."""
+    rng = np.random.default_rng(9)
+    for (M, K, N) in ((4, 7, 5), (9, 64, 33)):
+        X = rng.standard_normal((M, K)).astype(np.float32)
+        W = (rng.standard_normal((N, K)) / math.sqrt(K)).astype(np.float32)
+        b = rng.uniform(-0.5, 0.5, N).astype(np.float32)
+        s = rng.uniform(-0.5, 0.5, N).astype(np.float32)
+        out, rv = orc.linear_sub_rowmean_gelu_residual(X, W, b, s, with_rowval=True)
+        t = X.astype(np.float64) @ W.astype(np.float64).mean(axis=0) + (b.astype(np.float64) - s).mean()
+        g = np.array([_gelu_exact(float(v)) for v in t])
+        assert np.max(np.abs(rv - g)) < 1e-14
+        assert np.max(np.abs(out - (X.astype(np.float64) + g[:, None]))) < 1e-14
+
+
+def pin_rowmean_chain_by_hand(orc):
+    """M=2, K=2, N=3, every number written out."""
+    X = np.array([[1.0, 2.0], [-1.0, 0.5]], dtype=np.float32)
+    W = np.array([[1.0, 0.0], [0.0, 1.0], [2.0, -1.0]], dtype=np.float32)
+    b = np.array([0.5, 0.0, -0.5], dtype=np.float32)
+    s = np.array([0.0, 1.0, 0.5], dtype=np.float32)
+    # row 0: z = (1.5, 2, -0.5); z - s = (1.5, 1, -1); mean = 0.5
+    # row 1: z = (-0.5, 0.5, -3); z - s = (-0.5, -0.5, -3.5); mean = -1.5
+    means = [0.5, -1.5]
+    out, rv = orc.linear_sub_rowmean_gelu_residual(X, W, b, s, with_rowval=True)
+    for m in range(2):
+        g = _gelu_exact(means[m])
+        assert abs(rv[m] - g) < 1e-15
+        assert np.max(np.abs(out[m] - (X[m].astype(np.float64) + g))) < 1e-15
+    # optional vectors default to zero; W = 0 leaves only the bias/subtract mean
+    out0 = orc.linear_sub_rowmean_gelu_residual(X, np.zeros_like(W), b, s)
+    g0 = _gelu_exact(float((b.astype(np.float64) - s).mean()))
+    assert np.max(np.abs(out0 - (X.astype(np.float64) + g0))) < 1e-15
+    out1 = orc.linear_sub_rowmean_gelu_residual(X, W, None, None)
+    out2 = orc.linear_sub_rowmean_gelu_residual(X, W, np.zeros(3, np.float32), np.zeros(3, np.float32))
+    assert np.array_equal(out1, out2)
+
+
+def pin_rowmean_chain_library(orc):
+    """float64 library composition of the chain as stated, including a row subset."""
+    import torch.nn.functional as F
+    g = torch.Generator().manual_seed(10)
+    M, K, N = 11, 24, 40
+    X = torch.randn(M, K, generator=g); W = torch.randn(N, K, generator=g) / math.sqrt(K)
+    b = torch.rand(N, generator=g) - 0.5; s = torch.rand(N, generator=g) - 0.5
+    z = F.linear(X.double(), W.double(), b.double()) - s.double()
+    ref = (X.double() + F.gelu(z.mean(dim=1, keepdim=True), approximate="none")).numpy()
+    out = orc.linear_sub_rowmean_gelu_residual(X.numpy(), W.numpy(), b.numpy(), s.numpy())
+    assert np.max(np.abs(out - ref)) < 1e-13
+    sub = orc.linear_sub_rowmean_gelu_residual(X.numpy(), W.numpy(), b.numpy(), s.numpy(), rows=[10, 3, 3])
+    assert np.array_equal(sub, out[[10, 3, 3]])
+
+
+ALL_PINS += [pin_rowmean_chain_collapse, pin_rowmean_chain_by_hand, pin_rowmean_chain_library]

@@ -28,6 +28,10 @@ MUTANTS = [
     ("gamma_beta_swapped", "y[n] = (g[n] - mu) / denom * ga + be;", "y[n] = (g[n] - mu) / denom * be + ga;"),
     ("beta_dropped", "y[n] = (g[n] - mu) / denom * ga + be;", "y[n] = (g[n] - mu) / denom * ga;"),
     ("row_index", "const int64_t m = rows ? rows[r] : r;", "const int64_t m = r;"),
+    ("rowmean_subtract_dropped", "acc += z[n] - (s ? (double)s[n] : 0.0);", "acc += z[n];"),
+    ("rowmean_sum_not_mean", "const double g = oracle_gelu(acc / (double)N);", "const double g = oracle_gelu(acc);"),
+    ("rowmean_no_residual", "Out[(size_t)r * (size_t)K + k] = (double)x[k] + g;", "Out[(size_t)r * (size_t)K + k] = g;"),
+    ("rowmean_gelu_dropped", "const double g = oracle_gelu(acc / (double)N);", "const double g = acc / (double)N;"),
     ("bf16_truncates", "const double r = nearbyint(q);", "const double r = trunc(q);"),
     ("bf16_7bits", "ldexp(x, 7 - e)", "ldexp(x, 6 - e)"),
 ]
