@@ -60,7 +60,9 @@ def main() -> int:
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--workload", default="cfg1", help="cfg0..cfg4 (default: cfg1, the metric's workload)")
+    ap.add_argument("--workload", default="cfg1",
+                    help="cfg0..cfg4 (default: cfg1, the metric's workload), or rowmean "
+                         "(second fused chain: Linear, subtract, row-mean, GELU, residual add; bf16 4096^3)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-eager", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="target CPU time of the oracle sample")
@@ -85,6 +87,8 @@ def main() -> int:
         return 1
     B.load()  # fails loudly if the HIP library is not built
     torch.cuda.set_device(0)
+    if args.workload == "rowmean":
+        return bench_rowmean(args, torch, B)
     wl = CONFIGS[args.workload]
     M, K, N = wl.M, wl.K, wl.N
     esize = 4 if wl.dtype == "f32" else 2
@@ -196,6 +200,86 @@ def main() -> int:
         out["cpu_baseline"] = {"value": c_val, "unit": c_unit, "cores": threads, "kind": "oracle",
                                "sample": "%d of %d rows (complete rows, all N columns) in %.1f s; rate scaled to the full matrix"
                                          % (n_rows, M, c_s)}
+    print(json.dumps(out))
+    return 0
+
+
+def bench_rowmean(args, torch, B) -> int:
+    """Second fused chain on bf16 M = K = N = 4096: HBM-bound (W and X read once, Out written once)."""
+    import numpy as np
+    import torch.nn.functional as F
+    import oracle
+    from paper_2511_01884_amd.inputs import make_inputs
+
+    M = K = N = 4096
+    d = make_inputs(M, K, N, "bf16", seed=0)
+    g = torch.Generator(device="cpu").manual_seed(777)
+    s_vec = (torch.rand(N, generator=g) * 0.2 - 0.1).to(torch.bfloat16)
+    abytes = (N * K + 2 * M * K + 2 * N) * 2
+    n_sets = 5
+    b, sv = d["b"].cuda(), s_vec.cuda()
+    X0, W0 = d["X"].cuda(), d["W"].cuda()
+    sets = [(X0 if i == 0 else X0.clone(), W0 if i == 0 else W0.clone(), torch.empty_like(X0)) for i in range(n_sets)]
+
+    def step(i):
+        X, W, Out = sets[i % n_sets]
+        B.ff_fused_linear_sub_rowmean_gelu_residual(X, W, b, sv, Out=Out)
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    ev0 = torch.cuda.Event(enable_timing=True)
+    ev1 = torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    ev0.record()
+    for i in range(args.steps):
+        step(i)
+    ev1.record()
+    torch.cuda.synchronize()
+    ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
+    ms_kernel = ev0.elapsed_time(ev1) / args.steps
+    out = {
+        "metric": "TFLOP/s and % of bf16 MFMA peak (GB/s for small-M) for fused linear+GELU+LN",
+        "value": abytes / (ms_per_step * 1e-3) / 1e9, "unit": "GB/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "rowmean: bf16 Linear -> subtract -> row-mean -> GELU -> residual add, M=K=N=4096",
+                   "buffer_sets": n_sets, "algorithmic_mb_per_step": abytes / 1e6,
+                   "note": "three launches per step (column sums, column means, row pass)"},
+        "roofline": {"bound": "hbm", "achieved": abytes / (ms_kernel * 1e-3) / 1e9, "peak": PEAK_HBM_GBS,
+                     "unit": "GB/s", "frac": abytes / (ms_kernel * 1e-3) / 1e9 / PEAK_HBM_GBS, "traffic": None,
+                     "kernel_ms": ms_kernel},
+    }
+    if not args.no_eager:
+        def eager(i):
+            X, W, _ = sets[i % n_sets]
+            return X + F.gelu((F.linear(X, W, b) - sv).mean(dim=1, keepdim=True))
+        for i in range(5):
+            eager(i)
+        torch.cuda.synchronize()
+        e0 = time.perf_counter()
+        n_e = max(5, args.steps // 4)
+        for i in range(n_e):
+            eager(i)
+        torch.cuda.synchronize()
+        e_ms = (time.perf_counter() - e0) * 1e3 / n_e
+        out["pytorch_eager"] = {"ms_per_step": e_ms, "speedup_of_fused": e_ms / ms_per_step,
+                                "note": "unfused composition in bf16 on the same GPU (runs the full GEMM)"}
+    if not args.no_cpu_baseline:
+        arrs = [d["X"].float().numpy(), d["W"].float().numpy(), d["b"].float().numpy(), s_vec.float().numpy()]
+        threads = oracle.num_threads()
+        c0 = time.perf_counter()
+        oracle.linear_sub_rowmean_gelu_residual(*arrs, rows=list(range(threads)))
+        rows_per_s = threads / max(time.perf_counter() - c0, 1e-9)
+        n_rows = max(1, min(M, int(args.cpu_seconds * rows_per_s)))
+        rows = np.linspace(0, M - 1, n_rows).astype(np.int64)
+        c0 = time.perf_counter()
+        oracle.linear_sub_rowmean_gelu_residual(*arrs, rows=rows)
+        c_s = time.perf_counter() - c0
+        out["cpu_baseline"] = {"value": abytes * (n_rows / M) / c_s / 1e9, "unit": "GB/s", "cores": threads,
+                               "kind": "oracle",
+                               "sample": "%d of %d rows in %.1f s (the oracle evaluates the full linear layer per row); "
+                                         "rate scaled to the full matrix" % (n_rows, M, c_s)}
     print(json.dumps(out))
     return 0
 

@@ -91,6 +91,23 @@ int ff_fused_linear_gelu_ln(const void *X, const void *W, const void *b,
                             void *Y, void *stream);
 
 /*
+ * Second fused chain, the paper's fused-epilogue case study (App. B.1: Linear ->
+ * subtract -> row-mean -> GELU -> residual add):
+ *     Out[m][k] = X[m][k] + GELU( mean_n( X[m] . W[n] + b[n] - s[n] ) )
+ * X [M,K], W [N,K], b and s [N] (each may be NULL = 0), Out [M,K]; same dtype, layout,
+ * alignment, stream and error conventions as above; additionally K <= 32768.  Out may
+ * alias X (every row is read completely before it is written).  The row mean of a
+ * linear layer is one dot product with the column means of W, so this entry point
+ * reads W and X once and writes Out once; no GEMM is run.  Uses the workspace.
+ */
+int ff_fused_linear_sub_rowmean_gelu_residual(const void *X, const void *W, const void *b,
+                                              const void *s, int64_t M, int64_t K, int64_t N,
+                                              int dtype, void *Out, void *stream);
+
+/* Bytes of workspace the second chain needs for this shape (0 on invalid arguments). */
+size_t ff_rowmean_workspace_bytes(int64_t M, int64_t K, int64_t N, int dtype);
+
+/*
  * Bytes of workspace a call with this shape needs under the current variant
  * selection (0 on invalid arguments).  Pure host arithmetic.
  */

@@ -17,7 +17,8 @@ FF_OK = 0
 FF_VARIANT_AUTO, FF_VARIANT_TILED_FUSED, FF_VARIANT_TILED_TWOPASS, FF_VARIANT_SMALL_M = 0, 1, 2, 3
 
 EXPORTS = [
-    "ff_fused_linear_gelu_ln", "ff_workspace_bytes", "ff_set_workspace", "ff_check_device",
+    "ff_fused_linear_gelu_ln", "ff_fused_linear_sub_rowmean_gelu_residual", "ff_rowmean_workspace_bytes",
+    "ff_workspace_bytes", "ff_set_workspace", "ff_check_device",
     "ff_status_string", "ff_version", "ff_last_variant", "ff_debug_linear",
     "ff_debug_force_variant", "ff_debug_set_wait_limit_us", "ff_debug_expect_extra_arrivals",
 ]
@@ -43,6 +44,10 @@ def load() -> ctypes.CDLL:
         vp, i64, ci = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int
         lib.ff_fused_linear_gelu_ln.restype = ci
         lib.ff_fused_linear_gelu_ln.argtypes = [vp, vp, vp, vp, vp, ctypes.c_float, i64, i64, i64, ci, vp, vp]
+        lib.ff_fused_linear_sub_rowmean_gelu_residual.restype = ci
+        lib.ff_fused_linear_sub_rowmean_gelu_residual.argtypes = [vp, vp, vp, vp, i64, i64, i64, ci, vp, vp]
+        lib.ff_rowmean_workspace_bytes.restype = ctypes.c_size_t
+        lib.ff_rowmean_workspace_bytes.argtypes = [i64, i64, i64, ci]
         lib.ff_workspace_bytes.restype = ctypes.c_size_t
         lib.ff_workspace_bytes.argtypes = [i64, i64, i64, ci]
         lib.ff_set_workspace.restype = ci
@@ -161,6 +166,34 @@ def ff_fused_linear_gelu_ln(X: torch.Tensor, W: torch.Tensor, b: Optional[torch.
     if rc != FF_OK:
         raise FFError(rc)
     return Y
+
+
+def ff_fused_linear_sub_rowmean_gelu_residual(X: torch.Tensor, W: torch.Tensor, b: Optional[torch.Tensor],
+                                              s: Optional[torch.Tensor], Out: Optional[torch.Tensor] = None,
+                                              stream=None) -> torch.Tensor:
+    """Out = X + GELU(mean_n(X W^T + b - s)) on the device of X (allocates Out if not given)."""
+    if X.dim() != 2 or W.dim() != 2 or X.shape[1] != W.shape[1]:
+        raise ValueError("X must be [M,K] and W [N,K]")
+    M, K = X.shape
+    N = W.shape[0]
+    for v in (b, s):
+        if v is not None and tuple(v.shape) != (N,):
+            raise ValueError("b and s must have shape [N]")
+    if Out is None:
+        Out = torch.empty_like(X)
+    elif tuple(Out.shape) != (M, K):
+        raise ValueError("Out must be [M,K]")
+    with torch.cuda.device(X.device):
+        rc = load().ff_fused_linear_sub_rowmean_gelu_residual(
+            _ptr(X), _ptr(W, X), _ptr(b, X), _ptr(s, X), M, K, N, _dtype_code(X), _ptr(Out, X),
+            _stream(stream))
+    if rc != FF_OK:
+        raise FFError(rc)
+    return Out
+
+
+def ff_rowmean_workspace_bytes(M: int, K: int, N: int, dtype: int) -> int:
+    return int(load().ff_rowmean_workspace_bytes(M, K, N, dtype))
 
 
 def ff_debug_linear(X: torch.Tensor, W: torch.Tensor, b: Optional[torch.Tensor],

@@ -274,6 +274,89 @@ int ff_debug_linear(const void *X, const void *W, const void *b, int64_t M, int6
                static_cast<hipStream_t>(stream));
 }
 
+}  // extern "C"
+
+namespace {
+
+// Row chunks of the column-sum kernel: enough workgroups to keep HBM busy.
+void rowmean_plan(int64_t K, int64_t N, int dtype, int &chunks, int &rows_per_chunk)
+{
+    const int64_t per_strip = 128 * (dtype == FF_BF16 ? 8 : 4);
+    const int64_t strips = (K + per_strip - 1) / per_strip;
+    int64_t want = 1024 / strips;
+    if (want < 1)
+        want = 1;
+    if (want > (N + 7) / 8)
+        want = (N + 7) / 8;
+    rows_per_chunk = (int)((N + want - 1) / want);
+    chunks = (int)((N + rows_per_chunk - 1) / rows_per_chunk);
+}
+
+}  // namespace
+
+extern "C" {
+
+int ff_fused_linear_sub_rowmean_gelu_residual(const void *X, const void *W, const void *b, const void *s,
+                                              int64_t M, int64_t K, int64_t N, int dtype, void *Out,
+                                              void *stream)
+{
+    int rc = validate_shape(M, K, N, dtype);
+    if (rc != FF_OK)
+        return rc;
+    if (!X || !W || !Out)
+        return FF_ERR_NULL;
+    if (misaligned(X) || misaligned(W) || misaligned(b) || misaligned(s) || misaligned(Out))
+        return FF_ERR_ALIGN;
+    // rowdot keeps K floats of the column means in LDS
+    if (K > 32768)
+        return FF_ERR_UNSUPPORTED;
+    std::lock_guard<std::mutex> lock(g_mutex);
+    DeviceState *st = current_device_state();
+    if (!st)
+        return FF_ERR_LAUNCH;
+    RowMeanParams p{};
+    rowmean_plan(K, N, dtype, p.chunks, p.rows_per_chunk);
+    const size_t partial_bytes = round_up((size_t)p.chunks * (size_t)K * sizeof(float), 256);
+    const size_t wbar_bytes = round_up((size_t)(K + 1) * sizeof(float), 256);
+    rc = prepare_workspace(*st, kCtrlBytes + partial_bytes + wbar_bytes, static_cast<hipStream_t>(stream));
+    if (rc != FF_OK)
+        return rc;
+    char *ws = static_cast<char *>(st->ws);
+    p.X = X; p.W = W; p.b = b; p.s = s; p.Out = Out;
+    p.partial = reinterpret_cast<float *>(ws + kCtrlBytes);
+    p.wbar = reinterpret_cast<float *>(ws + kCtrlBytes + partial_bytes);
+    p.M = (int)M; p.K = (int)K; p.N = (int)N;
+    const int64_t groups = (M + 3) / 4;
+    const int64_t cap = (int64_t)st->num_cus * 8;
+    p.row_grid = (int)(groups < cap ? groups : cap);
+    if (launch_rowmean_chain(dtype == FF_BF16, p, static_cast<hipStream_t>(stream)) != hipSuccess)
+        return FF_ERR_LAUNCH;
+    return FF_OK;
+}
+
+}  // extern "C"
+
+namespace {
+
+size_t rowmean_workspace_bytes(int64_t K, int64_t N, int dtype)
+{
+    int chunks, rpc;
+    rowmean_plan(K, N, dtype, chunks, rpc);
+    return kCtrlBytes + round_up((size_t)chunks * (size_t)K * sizeof(float), 256) +
+           round_up((size_t)(K + 1) * sizeof(float), 256);
+}
+
+}  // namespace
+
+extern "C" {
+
+size_t ff_rowmean_workspace_bytes(int64_t M, int64_t K, int64_t N, int dtype)
+{
+    if (validate_shape(M, K, N, dtype) != FF_OK)
+        return 0;
+    return rowmean_workspace_bytes(K, N, dtype);
+}
+
 size_t ff_workspace_bytes(int64_t M, int64_t K, int64_t N, int dtype)
 {
     if (validate_shape(M, K, N, dtype) != FF_OK)

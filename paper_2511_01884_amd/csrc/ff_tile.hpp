@@ -52,6 +52,17 @@ struct SmallMParams {
     long long wait_ticks;
 };
 
+struct RowMeanParams {
+    const void *X, *W, *b, *s;
+    void *Out;
+    float *partial;      // [chunks][K] partial column sums of W
+    float *wbar;         // [K + 1]: column means of W, then c = mean(b - s)
+    int M, K, N;
+    int chunks, rows_per_chunk;
+    int row_grid;
+};
+
+hipError_t launch_rowmean_chain(bool bf16, const RowMeanParams &p, hipStream_t stream);
 hipError_t launch_tile_kernel(bool bf16, int tile, int mode, const TileParams &p, int grid,
                               hipStream_t stream);
 hipError_t launch_finalize_kernel(bool bf16, const FinalizeParams &p, hipStream_t stream);
