@@ -283,12 +283,11 @@ void rowmean_plan(int64_t K, int64_t N, int dtype, int &chunks, int &rows_per_ch
 {
     const int64_t per_strip = 128 * (dtype == FF_BF16 ? 8 : 4);
     const int64_t strips = (K + per_strip - 1) / per_strip;
-    int64_t want = 1024 / strips;
+    int64_t want = 256 / strips;
     if (want < 1)
         want = 1;
-    if (want > (N + 7) / 8)
-        want = (N + 7) / 8;
-    rows_per_chunk = (int)((N + want - 1) / want);
+    const int64_t quantum = 8 * kRowMeanColSub;  // every row group of a workgroup gets whole batches of 8 rows
+    rows_per_chunk = (int)(((N + want - 1) / want + quantum - 1) / quantum * quantum);
     chunks = (int)((N + rows_per_chunk - 1) / rows_per_chunk);
 }
 
@@ -326,8 +325,8 @@ int ff_fused_linear_sub_rowmean_gelu_residual(const void *X, const void *W, cons
     p.partial = reinterpret_cast<float *>(ws + kCtrlBytes);
     p.wbar = reinterpret_cast<float *>(ws + kCtrlBytes + partial_bytes);
     p.M = (int)M; p.K = (int)K; p.N = (int)N;
-    const int64_t groups = (M + 3) / 4;
-    const int64_t cap = (int64_t)st->num_cus * 8;
+    const int64_t groups = (M + kRowMeanWaves - 1) / kRowMeanWaves;
+    const int64_t cap = (int64_t)st->num_cus * 4;
     p.row_grid = (int)(groups < cap ? groups : cap);
     if (launch_rowmean_chain(dtype == FF_BF16, p, static_cast<hipStream_t>(stream)) != hipSuccess)
         return FF_ERR_LAUNCH;

@@ -52,6 +52,11 @@ struct SmallMParams {
     long long wait_ticks;
 };
 
+// wavefronts (one row each) per workgroup of the row pass of the second chain
+constexpr int kRowMeanWaves = 8;
+// row groups per workgroup of its column-sum pass: rows_per_chunk is a multiple of 8 times this
+constexpr int kRowMeanColSub = 4;
+
 struct RowMeanParams {
     const void *X, *W, *b, *s;
     void *Out;
