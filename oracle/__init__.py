@@ -8,6 +8,7 @@ from .oracle import (  # noqa: F401
     Oracle,
     SOURCE,
     build,
+    cross_entropy,
     fused_linear_gelu_ln,
     gelu,
     layernorm_row,

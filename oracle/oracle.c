@@ -31,6 +31,9 @@
  * float64 library composition.  The second chain at the end of this file is
  * pinned by the algebraic collapse of its row mean to one dot product (evaluated
  * independently in the test), a hand-expanded case, special cases and a library
+ * composition.  The row-wise cross-entropy at the end is pinned by closed forms
+ * (equal logits, two classes, logits that are logs of small integers), shift
+ * invariance, an overflow case, hand-expanded tiny cases and a library
  * composition.  No function here is unpinned.
  *
  * Build: gcc -O2 -fno-fast-math -ffp-contract=off -fopenmp -shared -fPIC
@@ -242,4 +245,54 @@ int oracle_linear_sub_rowmean_gelu_residual(const float *X, const float *W, cons
         free(z);
     }
     return failed ? -1 : 0;
+}
+
+/* ---------------------------------------------------------------------------
+ * Row-wise cross-entropy, the row reduction of the paper's case study (Sec. 4:
+ * a row maximum, a sum of exponentials, and the pick of the target's logit):
+ *
+ *     loss[r] = log( sum_c exp(L[r][c]) ) - L[r][t[r]],     mean = (1/B) sum_r loss[r]
+ *
+ * The log-sum-exp is evaluated the standard overflow-free way, exactly the
+ * three phases the case study names: mx = max_c L[r][c];
+ * se = sum_c exp(L[r][c] - mx);  loss = mx + log(se) - L[r][t].
+ *   L [B,C] fp32 (bf16 inputs are widened exactly by the caller), t [B] int64.
+ *   A target outside [0, C) makes that row's loss NaN (and with it the mean).
+ *   row_loss [B] fp64 optional; *mean_loss fp64 optional.  Sums in index order.
+ */
+int oracle_cross_entropy(const float *L, const int64_t *t, int64_t B, int64_t C,
+                         double *row_loss, double *mean_loss)
+{
+    if (!L || !t || B <= 0 || C <= 0)
+        return -1;
+    double *loss = row_loss;
+    if (!loss) {
+        loss = (double *)malloc((size_t)B * sizeof(double));
+        if (!loss)
+            return -1;
+    }
+#pragma omp parallel for schedule(static)
+    for (int64_t r = 0; r < B; ++r) {
+        const float *row = L + (size_t)r * (size_t)C;
+        double mx = (double)row[0];
+        for (int64_t c = 1; c < C; ++c)
+            if ((double)row[c] > mx)
+                mx = (double)row[c];
+        double se = 0.0;
+        for (int64_t c = 0; c < C; ++c)
+            se += exp((double)row[c] - mx);
+        if (t[r] < 0 || t[r] >= C)
+            loss[r] = NAN;
+        else
+            loss[r] = mx + log(se) - (double)row[t[r]];
+    }
+    if (mean_loss) {
+        double acc = 0.0;
+        for (int64_t r = 0; r < B; ++r)
+            acc += loss[r];
+        *mean_loss = acc / (double)B;
+    }
+    if (!row_loss)
+        free(loss);
+    return 0;
 }

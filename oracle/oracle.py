@@ -49,6 +49,8 @@ def _bind(path: str):
     lib.oracle_round_bf16.argtypes = [dp, i64, dp]
     lib.oracle_linear_sub_rowmean_gelu_residual.restype = ctypes.c_int
     lib.oracle_linear_sub_rowmean_gelu_residual.argtypes = [fp, fp, fp, fp, i64, i64, i64, ip, i64, dp, dp]
+    lib.oracle_cross_entropy.restype = ctypes.c_int
+    lib.oracle_cross_entropy.argtypes = [fp, ip, i64, i64, dp, dp]
     return lib
 
 
@@ -175,6 +177,21 @@ class Oracle:
             raise RuntimeError("oracle_linear_sub_rowmean_gelu_residual failed (rc=%d)" % rc)
         return (Out, rv) if with_rowval else Out
 
+    def cross_entropy(self, logits, targets):
+        """(row_loss float64 [B], mean float) of the row-wise cross-entropy of logits [B,C], targets [B]."""
+        L = _f32(logits)
+        B, C = L.shape
+        t = np.ascontiguousarray(targets, dtype=np.int64)
+        if t.shape != (B,):
+            raise ValueError("targets must be [B]")
+        rl = np.empty(B, dtype=np.float64)
+        mean = ctypes.c_double(0.0)
+        rc = self._lib.oracle_cross_entropy(_ptr(L, ctypes.c_float), _ptr(t, ctypes.c_int64), B, C,
+                                            _ptr(rl, ctypes.c_double), ctypes.byref(mean))
+        if rc != 0:
+            raise RuntimeError("oracle_cross_entropy failed (rc=%d)" % rc)
+        return rl, float(mean.value)
+
     def round_bf16(self, a) -> np.ndarray:
         """Nearest bfloat16 value (ties to even) of each fp64 element, as float64."""
         a = np.ascontiguousarray(a, dtype=np.float64)
@@ -216,6 +233,10 @@ def fused_linear_gelu_ln(X, W, b=None, gamma=None, beta=None, eps: float = 1e-5,
 
 def linear_sub_rowmean_gelu_residual(X, W, b=None, s=None, rows=None, with_rowval: bool = False):
     return _get().linear_sub_rowmean_gelu_residual(X, W, b, s, rows, with_rowval)
+
+
+def cross_entropy(logits, targets):
+    return _get().cross_entropy(logits, targets)
 
 
 def round_bf16(a):

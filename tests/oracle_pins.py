@@ -328,3 +328,87 @@ def pin_rowmean_chain_library(orc):
 
 
 ALL_PINS += [pin_rowmean_chain_collapse, pin_rowmean_chain_by_hand, pin_rowmean_chain_library]
+
+
+# ------------------------------------------------- row-wise cross-entropy
+def pin_xent_closed_forms(orc):
+    """Equal logits give log C whatever the target; logits that are logs of 1..C give
+    log(C(C+1)/2) - log(t+1); two classes give softplus of the logit difference."""
+    for C in (1, 2, 7, 64):
+        for v in (0.0, -3.5, 1000.0):  # 1000: exp overflows unless the maximum is removed first
+            L = np.full((3, C), v, dtype=np.float32)
+            t = np.array([0, C - 1, C // 2])
+            rl, mean = orc.cross_entropy(L, t)
+            assert np.allclose(rl, math.log(C), rtol=0, atol=1e-12), (C, v, rl)
+            assert abs(mean - math.log(C)) < 1e-12
+    C = 9
+    row = np.log(np.arange(1, C + 1, dtype=np.float64)).astype(np.float32)  # rounded once; use the rounded values
+    L = np.tile(row, (C, 1))
+    t = np.arange(C)
+    rl, mean = orc.cross_entropy(L, t)
+    tot = math.fsum(math.exp(float(x)) for x in row)
+    want = np.array([math.log(tot) - float(row[c]) for c in range(C)])
+    assert np.allclose(rl, want, rtol=0, atol=1e-12)
+    assert abs(tot - 45.0) < 1e-5  # 1 + 2 + ... + 9, up to the float32 rounding of the logs
+    assert abs(mean - math.fsum(want) / C) < 1e-12
+    # two classes: loss = log(1 + exp(-(L_t - L_other)))
+    d = np.array([-30.0, -2.0, -0.25, 0.0, 0.5, 3.0, 40.0], dtype=np.float32)
+    L = np.stack([d, np.zeros_like(d)], axis=1)
+    rl, _ = orc.cross_entropy(L, np.zeros(len(d), dtype=np.int64))
+    want = np.array([math.log1p(math.exp(-float(x))) if x > -20 else -float(x) + math.log1p(math.exp(float(x)))
+                     for x in d])
+    assert np.allclose(rl, want, rtol=1e-13, atol=1e-15), (rl, want)
+    rl1, _ = orc.cross_entropy(L, np.ones(len(d), dtype=np.int64))
+    assert np.allclose(rl1 - rl, d.astype(np.float64), rtol=0, atol=1e-12)  # the two losses differ by the logit gap
+
+
+def pin_xent_by_hand(orc):
+    """Non-square hand case: distinct targets per row, mean over rows (not classes)."""
+    L = np.array([[1.0, 2.0, 0.5, -1.0, 0.0],
+                  [-2.0, 0.25, 0.25, 3.0, 1.5]], dtype=np.float32)
+    t = np.array([3, 1])
+    r0 = math.log(math.exp(1.0) + math.exp(2.0) + math.exp(0.5) + math.exp(-1.0) + math.exp(0.0)) - (-1.0)
+    r1 = math.log(math.exp(-2.0) + 2 * math.exp(0.25) + math.exp(3.0) + math.exp(1.5)) - 0.25
+    rl, mean = orc.cross_entropy(L, t)
+    assert abs(rl[0] - r0) < 1e-13 and abs(rl[1] - r1) < 1e-13, (rl, r0, r1)
+    assert abs(mean - (r0 + r1) / 2) < 1e-13
+    # a target outside [0, C) poisons its row and the mean, nothing else
+    rl, mean = orc.cross_entropy(L, np.array([5, 1]))
+    assert math.isnan(rl[0]) and abs(rl[1] - r1) < 1e-13 and math.isnan(mean)
+    rl, _ = orc.cross_entropy(L, np.array([-1, 1]))
+    assert math.isnan(rl[0])
+
+
+def pin_xent_shift_and_library(orc):
+    """Adding a constant to a row changes nothing; the maximum may sit anywhere in the row;
+    agreement with an independent float64 library composition on random inputs."""
+    g = torch.Generator(device="cpu").manual_seed(11)
+    B, C = 37, 203
+    L = torch.round(torch.randn(B, C, generator=g) * 3.0 * 1024.0) / 1024.0  # multiples of 2^-10
+    t = torch.randint(0, C, (B,), generator=g)
+    rl, mean = orc.cross_entropy(L.numpy(), t.numpy())
+    # the shifted logits are exact in float32, so the shifted problem is the same problem
+    Ls = (L.double() + 64.0).float()
+    assert bool((Ls.double() - 64.0 == L.double()).all())
+    rls, _ = orc.cross_entropy(Ls.numpy(), t.numpy())
+    assert np.allclose(rls, rl, rtol=0, atol=1e-11)
+    want = torch.nn.functional.cross_entropy(L.double(), t, reduction="none").numpy()
+    assert np.allclose(rl, want, rtol=0, atol=1e-12)
+    assert abs(mean - float(torch.nn.functional.cross_entropy(L.double(), t))) < 1e-12
+    lse = torch.logsumexp(L.double(), dim=1).numpy()
+    assert np.allclose(rl, lse - L.double().numpy()[np.arange(B), t.numpy()], rtol=0, atol=1e-12)
+    # one logit so large that exp overflows unless exactly that maximum is removed, at either end and inside
+    for pos in (0, 3, 6):
+        Lh = np.zeros((2, 7), dtype=np.float32)
+        Lh[:, pos] = 1000.0
+        rlh, _ = orc.cross_entropy(Lh, np.array([pos, (pos + 1) % 7]))
+        assert rlh[0] == 0.0 and rlh[1] == 1000.0, (pos, rlh)
+    # maximum in the first, a middle and the last position
+    for pos in (0, C // 2, C - 1):
+        L2 = L.clone()
+        L2[:, pos] = 50.0
+        rl2, _ = orc.cross_entropy(L2.numpy(), np.full(B, pos))
+        assert np.all(rl2 >= 0) and np.all(rl2 < 1e-15 + C * math.exp(-35.0)), rl2.max()
+
+
+ALL_PINS += [pin_xent_closed_forms, pin_xent_by_hand, pin_xent_shift_and_library]

@@ -32,6 +32,16 @@ MUTANTS = [
     ("rowmean_sum_not_mean", "const double g = oracle_gelu(acc / (double)N);", "const double g = oracle_gelu(acc);"),
     ("rowmean_no_residual", "Out[(size_t)r * (size_t)K + k] = (double)x[k] + g;", "Out[(size_t)r * (size_t)K + k] = g;"),
     ("rowmean_gelu_dropped", "const double g = oracle_gelu(acc / (double)N);", "const double g = acc / (double)N;"),
+    ("xent_max_not_removed", "se += exp((double)row[c] - mx);", "se += exp((double)row[c]);"),
+    ("xent_max_skips_last", "for (int64_t c = 1; c < C; ++c)\n            if ((double)row[c] > mx)",
+     "for (int64_t c = 1; c < C - 1; ++c)\n            if ((double)row[c] > mx)"),
+    ("xent_max_not_added_back", "loss[r] = mx + log(se) - (double)row[t[r]];", "loss[r] = log(se) - (double)row[t[r]];"),
+    ("xent_pick_from_row_index", "loss[r] = mx + log(se) - (double)row[t[r]];",
+     "loss[r] = mx + log(se) - (double)row[r % C];"),
+    ("xent_sign", "loss[r] = mx + log(se) - (double)row[t[r]];", "loss[r] = (double)row[t[r]] - mx - log(se);"),
+    ("xent_log2", "loss[r] = mx + log(se) - (double)row[t[r]];", "loss[r] = mx + log2(se) - (double)row[t[r]];"),
+    ("xent_mean_over_classes", "*mean_loss = acc / (double)B;", "*mean_loss = acc / (double)C;"),
+    ("xent_target_bound", "if (t[r] < 0 || t[r] >= C)", "if (t[r] < 0 || t[r] > C)"),
     ("bf16_truncates", "const double r = nearbyint(q);", "const double r = trunc(q);"),
     ("bf16_7bits", "ldexp(x, 7 - e)", "ldexp(x, 6 - e)"),
 ]
