@@ -91,6 +91,26 @@ int ff_fused_linear_gelu_ln(const void *X, const void *W, const void *b,
                             void *Y, void *stream);
 
 /*
+ * Row-wise cross-entropy with mean reduction, the row reduction of the paper's case
+ * study (Sec. 4: row maximum, sum of exponentials, pick of the target's logit):
+ *     loss[r] = log( sum_c exp(L[r][c]) ) - L[r][t[r]],   *mean_loss = (1/B) sum_r loss[r]
+ *   logits   device, [B,C] row-major, dtype FF_F32 or FF_BF16, 16-byte aligned, read once.
+ *            Any C >= 1 (rows whose byte length is a multiple of 16 use 16-byte loads).
+ *   targets  device, [B] int64 class indices.  A target outside [0, C) makes that row's
+ *            loss, and the mean, NaN; nothing is read out of bounds.
+ *   row_loss device, [B] fp32, optional (NULL): the per-row losses.
+ *   mean_loss device, one fp32, required.
+ * Arithmetic is fp32 whatever the input dtype.  Asynchronous on `stream`; uses the
+ * workspace (one number per workgroup and an arrival counter).  Results are bitwise
+ * reproducible on a given device.  Returns an ff_status.
+ */
+int ff_cross_entropy_mean(const void *logits, const int64_t *targets, int64_t B, int64_t C,
+                          int dtype, float *row_loss, float *mean_loss, void *stream);
+
+/* Workspace bytes ff_cross_entropy_mean needs (0 for an invalid shape). */
+size_t ff_cross_entropy_workspace_bytes(int64_t B, int64_t C, int dtype);
+
+/*
  * Second fused chain, the paper's fused-epilogue case study (App. B.1: Linear ->
  * subtract -> row-mean -> GELU -> residual add):
  *     Out[m][k] = X[m][k] + GELU( mean_n( X[m] . W[n] + b[n] - s[n] ) )

@@ -18,6 +18,7 @@ FF_VARIANT_AUTO, FF_VARIANT_TILED_FUSED, FF_VARIANT_TILED_TWOPASS, FF_VARIANT_SM
 
 EXPORTS = [
     "ff_fused_linear_gelu_ln", "ff_fused_linear_sub_rowmean_gelu_residual", "ff_rowmean_workspace_bytes",
+    "ff_cross_entropy_mean", "ff_cross_entropy_workspace_bytes",
     "ff_workspace_bytes", "ff_set_workspace", "ff_check_device",
     "ff_status_string", "ff_version", "ff_last_variant", "ff_debug_linear",
     "ff_debug_force_variant", "ff_debug_set_wait_limit_us", "ff_debug_expect_extra_arrivals",
@@ -48,6 +49,10 @@ def load() -> ctypes.CDLL:
         lib.ff_fused_linear_sub_rowmean_gelu_residual.argtypes = [vp, vp, vp, vp, i64, i64, i64, ci, vp, vp]
         lib.ff_rowmean_workspace_bytes.restype = ctypes.c_size_t
         lib.ff_rowmean_workspace_bytes.argtypes = [i64, i64, i64, ci]
+        lib.ff_cross_entropy_mean.restype = ci
+        lib.ff_cross_entropy_mean.argtypes = [vp, vp, i64, i64, ci, vp, vp, vp]
+        lib.ff_cross_entropy_workspace_bytes.restype = ctypes.c_size_t
+        lib.ff_cross_entropy_workspace_bytes.argtypes = [i64, i64, ci]
         lib.ff_workspace_bytes.restype = ctypes.c_size_t
         lib.ff_workspace_bytes.argtypes = [i64, i64, i64, ci]
         lib.ff_set_workspace.restype = ci
@@ -194,6 +199,38 @@ def ff_fused_linear_sub_rowmean_gelu_residual(X: torch.Tensor, W: torch.Tensor, 
 
 def ff_rowmean_workspace_bytes(M: int, K: int, N: int, dtype: int) -> int:
     return int(load().ff_rowmean_workspace_bytes(M, K, N, dtype))
+
+
+def ff_cross_entropy_mean(logits: torch.Tensor, targets: torch.Tensor, row_loss: Optional[torch.Tensor] = None,
+                          mean_loss: Optional[torch.Tensor] = None, with_rows: bool = False, stream=None):
+    """Mean over rows of log(sum_c exp(L[r][c])) - L[r][t[r]]; returns the one-element fp32 tensor,
+    or (mean, row_loss) when per-row losses are asked for.  Output tensors are allocated if not given."""
+    if logits.dim() != 2 or targets.dim() != 1 or targets.shape[0] != logits.shape[0]:
+        raise ValueError("logits must be [B,C] and targets [B]")
+    if targets.dtype != torch.int64 or not targets.is_cuda or not targets.is_contiguous() \
+            or targets.device != logits.device:
+        raise ValueError("targets must be a contiguous int64 tensor on the device of logits")
+    B, C = logits.shape
+    if mean_loss is None:
+        mean_loss = torch.empty(1, dtype=torch.float32, device=logits.device)
+    if row_loss is None and with_rows:
+        row_loss = torch.empty(B, dtype=torch.float32, device=logits.device)
+    for v, n in ((mean_loss, 1), (row_loss, B)):
+        if v is not None and (v.dtype != torch.float32 or v.numel() != n or v.device != logits.device
+                              or not v.is_contiguous()):
+            raise ValueError("loss outputs must be contiguous float32 tensors of 1 and B elements")
+    with torch.cuda.device(logits.device):
+        rc = load().ff_cross_entropy_mean(
+            _ptr(logits), ctypes.c_void_p(targets.data_ptr()), B, C, _dtype_code(logits),
+            None if row_loss is None else ctypes.c_void_p(row_loss.data_ptr()),
+            ctypes.c_void_p(mean_loss.data_ptr()), _stream(stream))
+    if rc != FF_OK:
+        raise FFError(rc)
+    return (mean_loss, row_loss) if row_loss is not None else mean_loss
+
+
+def ff_cross_entropy_workspace_bytes(B: int, C: int, dtype: int) -> int:
+    return int(load().ff_cross_entropy_workspace_bytes(B, C, dtype))
 
 
 def ff_debug_linear(X: torch.Tensor, W: torch.Tensor, b: Optional[torch.Tensor],

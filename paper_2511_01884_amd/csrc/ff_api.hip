@@ -91,7 +91,7 @@ int make_plan(int64_t M, int64_t K, int64_t N, int dtype, int num_cus, int force
     pl.tile = tiles256 * 2 >= num_cus ? 256 : 128;
     const int64_t RB = (M + pl.tile - 1) / pl.tile;
     const int64_t NT = (N + pl.tile - 1) / pl.tile;
-    if (RB > kMaxRowBlocks || RB * NT > (int64_t)1 << 30)
+    if (RB > kMaxRowBlocks - 1 || RB * NT > (int64_t)1 << 30)  // the last counter pair belongs to the cross-entropy kernel
         return FF_ERR_SHAPE;
     pl.RB = (int)RB;
     pl.NT = (int)NT;
@@ -354,6 +354,57 @@ size_t ff_rowmean_workspace_bytes(int64_t M, int64_t K, int64_t N, int dtype)
     if (validate_shape(M, K, N, dtype) != FF_OK)
         return 0;
     return rowmean_workspace_bytes(K, N, dtype);
+}
+
+int ff_cross_entropy_mean(const void *logits, const int64_t *targets, int64_t B, int64_t C, int dtype,
+                          float *row_loss, float *mean_loss, void *stream)
+{
+    if (dtype != FF_F32 && dtype != FF_BF16)
+        return FF_ERR_DTYPE;
+    if (B <= 0 || C <= 0 || B > (int64_t)1 << 30 || C > (int64_t)1 << 30)
+        return FF_ERR_SHAPE;
+    if (!logits || !targets || !mean_loss)
+        return FF_ERR_NULL;
+    if (misaligned(logits) || (reinterpret_cast<uintptr_t>(targets) & 7u) ||
+        (reinterpret_cast<uintptr_t>(row_loss) & 3u) || (reinterpret_cast<uintptr_t>(mean_loss) & 3u))
+        return FF_ERR_ALIGN;
+    std::lock_guard<std::mutex> lock(g_mutex);
+    DeviceState *st = current_device_state();
+    if (!st)
+        return FF_ERR_LAUNCH;
+    XentParams p{};
+    const int64_t row_bytes = C * (dtype == FF_BF16 ? 2 : 4);
+    // a wavefront per row while there are rows enough to fill the chip and a row is short;
+    // otherwise the whole workgroup shares a row
+    p.wg_per_row = (row_bytes >= 64 * 1024 || B < (int64_t)st->num_cus * 16) ? 1 : 0;
+    const int64_t groups = p.wg_per_row ? B : (B + 3) / 4;
+    const int64_t cap = (int64_t)st->num_cus * 8;
+    p.grid = (int)(groups < cap ? groups : cap);
+    const int rc = prepare_workspace(*st, kCtrlBytes + round_up((size_t)p.grid * sizeof(floatx2), 256),
+                                     static_cast<hipStream_t>(stream));
+    if (rc != FF_OK)
+        return rc;
+    char *ws = static_cast<char *>(st->ws);
+    p.logits = logits;
+    p.targets = reinterpret_cast<const long long *>(targets);
+    p.row_loss = row_loss;
+    p.mean_loss = mean_loss;
+    p.partials = reinterpret_cast<floatx2 *>(ws + kCtrlBytes);
+    // the last counter pair of the control region; the tiled kernels never reach it
+    p.counter = reinterpret_cast<unsigned *>(ws + kCounterOffset) + 2 * (kMaxRowBlocks - 1);
+    p.B = (int)B;
+    p.C = (int)C;
+    if (launch_xent_kernel(dtype == FF_BF16, p, static_cast<hipStream_t>(stream)) != hipSuccess)
+        return FF_ERR_LAUNCH;
+    return FF_OK;
+}
+
+size_t ff_cross_entropy_workspace_bytes(int64_t B, int64_t C, int dtype)
+{
+    if ((dtype != FF_F32 && dtype != FF_BF16) || B <= 0 || C <= 0)
+        return 0;
+    // sized for the largest grid any device uses here (8 workgroups per compute unit, 1024 units)
+    return kCtrlBytes + 8192 * sizeof(floatx2);
 }
 
 size_t ff_workspace_bytes(int64_t M, int64_t K, int64_t N, int dtype)

@@ -67,6 +67,19 @@ struct RowMeanParams {
     int row_grid;
 };
 
+struct XentParams {
+    const void *logits;        // [B][C]
+    const long long *targets;  // [B]
+    float *row_loss;           // [B] or null
+    float *mean_loss;          // [1]
+    floatx2 *partials;         // [grid]: one number per workgroup (second component unused)
+    unsigned *counter;         // arrivals of this launch; zero before and after
+    int B, C;
+    int grid;
+    int wg_per_row;            // 1: a workgroup per row (long rows, few rows); 0: a wavefront per row
+};
+
+hipError_t launch_xent_kernel(bool bf16, const XentParams &p, hipStream_t stream);
 hipError_t launch_rowmean_chain(bool bf16, const RowMeanParams &p, hipStream_t stream);
 hipError_t launch_tile_kernel(bool bf16, int tile, int mode, const TileParams &p, int grid,
                               hipStream_t stream);

@@ -90,6 +90,16 @@ def make_integer_inputs(M: int, K: int, N: int, dtype: str = "bf16", seed: int =
     return {"X": X.contiguous(), "W": W.contiguous(), "b": b.contiguous()}
 
 
+def make_xent_inputs(B: int, C: int, dtype: str = "f32", seed: int = 0, scale: float = 1.0):
+    """Logits ~ scale * N(0, 1) [B, C] rounded to the storage dtype, targets uniform in [0, C)
+    (int64), drawn in that order from one host stream: the shape of input the paper's row-reduction
+    case study (Sec. 4) runs on, a batch of score rows and one class index per row."""
+    g = torch.Generator(device="cpu").manual_seed(seed)
+    logits = (torch.randn(B, C, generator=g, dtype=torch.float32) * scale).to(torch_dtype(dtype))
+    targets = torch.randint(0, C, (B,), generator=g, dtype=torch.int64)
+    return logits, targets
+
+
 def sample_rows(M: int, n: int, tile: int = 256, seed: int = 0):
     """Row indices for sampled checks at full size: the rows next to tile
     boundaries plus seeded random rows, sorted and unique."""
