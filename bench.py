@@ -62,7 +62,8 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="cfg1",
                     help="cfg0..cfg4 (default: cfg1, the metric's workload), or rowmean "
-                         "(second fused chain: Linear, subtract, row-mean, GELU, residual add; bf16 4096^3)")
+                         "(second fused chain: Linear, subtract, row-mean, GELU, residual add; bf16 4096^3), or xent "
+                         "(row-wise cross-entropy with mean, fp32 32768 x 4096)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-eager", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="target CPU time of the oracle sample")
@@ -89,6 +90,8 @@ def main() -> int:
     torch.cuda.set_device(0)
     if args.workload == "rowmean":
         return bench_rowmean(args, torch, B)
+    if args.workload == "xent":
+        return bench_xent(args, torch, B)
     wl = CONFIGS[args.workload]
     M, K, N = wl.M, wl.K, wl.N
     esize = 4 if wl.dtype == "f32" else 2
@@ -280,6 +283,77 @@ def bench_rowmean(args, torch, B) -> int:
                                "kind": "oracle",
                                "sample": "%d of %d rows in %.1f s (the oracle evaluates the full linear layer per row); "
                                          "rate scaled to the full matrix" % (n_rows, M, c_s)}
+    print(json.dumps(out))
+    return 0
+
+
+def bench_xent(args, torch, B) -> int:
+    """Row-wise cross-entropy with mean on fp32 logits [32768, 4096]: HBM-bound, the logits are read once."""
+    import torch.nn.functional as F
+    import oracle
+    from paper_2511_01884_amd.inputs import make_xent_inputs
+
+    Bn, C = 32768, 4096
+    logits, targets = make_xent_inputs(Bn, C, "f32", seed=0)
+    abytes = Bn * C * 4 + Bn * 8 + 4  # logits and targets read once, the mean written
+    n_sets = 2
+    sets = [(logits.cuda(), targets.cuda(), torch.empty(1, device="cuda")) for _ in range(n_sets)]
+
+    def step(i):
+        L, t, out = sets[i % n_sets]
+        B.ff_cross_entropy_mean(L, t, mean_loss=out)
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    ev0 = torch.cuda.Event(enable_timing=True)
+    ev1 = torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    ev0.record()
+    for i in range(args.steps):
+        step(i)
+    ev1.record()
+    torch.cuda.synchronize()
+    ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
+    ms_kernel = ev0.elapsed_time(ev1) / args.steps
+    out = {
+        "metric": "TFLOP/s and % of bf16 MFMA peak (GB/s for small-M) for fused linear+GELU+LN",
+        "value": abytes / (ms_per_step * 1e-3) / 1e9, "unit": "GB/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": "xent: row-wise cross-entropy with mean, fp32 logits [32768, 4096], int64 targets",
+                   "buffer_sets": n_sets, "algorithmic_mb_per_step": abytes / 1e6},
+        "roofline": {"bound": "hbm", "achieved": abytes / (ms_kernel * 1e-3) / 1e9, "peak": PEAK_HBM_GBS,
+                     "unit": "GB/s", "frac": abytes / (ms_kernel * 1e-3) / 1e9 / PEAK_HBM_GBS, "traffic": None,
+                     "kernel_ms": ms_kernel},
+    }
+    if not args.no_eager:
+        def eager(i):
+            L, t, _ = sets[i % n_sets]
+            return F.cross_entropy(L, t)
+        for i in range(5):
+            eager(i)
+        torch.cuda.synchronize()
+        e0 = time.perf_counter()
+        n_e = max(5, args.steps // 4)
+        for i in range(n_e):
+            eager(i)
+        torch.cuda.synchronize()
+        e_ms = (time.perf_counter() - e0) * 1e3 / n_e
+        out["pytorch_eager"] = {"ms_per_step": e_ms, "speedup_of_fused": e_ms / ms_per_step,
+                                "note": "torch.nn.functional.cross_entropy on the same GPU"}
+    if not args.no_cpu_baseline:
+        threads = oracle.num_threads()
+        Ln, tn = logits.numpy(), targets.numpy()
+        c0 = time.perf_counter()
+        oracle.cross_entropy(Ln[:1024], tn[:1024])
+        rows_per_s = 1024 / max(time.perf_counter() - c0, 1e-9)
+        n_rows = max(1024, min(Bn, int(args.cpu_seconds * rows_per_s)))
+        c0 = time.perf_counter()
+        oracle.cross_entropy(Ln[:n_rows], tn[:n_rows])
+        c_s = time.perf_counter() - c0
+        out["cpu_baseline"] = {"value": abytes * (n_rows / Bn) / c_s / 1e9, "unit": "GB/s", "cores": threads,
+                               "kind": "oracle", "sample": "first %d of %d rows in %.2f s" % (n_rows, Bn, c_s)}
     print(json.dumps(out))
     return 0
 
