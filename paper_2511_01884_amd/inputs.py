@@ -35,13 +35,15 @@ class Workload:
     note: str
 
 
-# The five synthetic workloads the build is measured on.
+# The synthetic workloads the build is measured on: five for the main metric, then the
+# fp32 path at a large shape.
 CONFIGS: Dict[str, Workload] = {
     "cfg0": Workload("cfg0", "f32", 256, 512, 512, "fp32 parity case"),
     "cfg1": Workload("cfg1", "bf16", 4096, 4096, 4096, "compute-bound square case"),
     "cfg2": Workload("cfg2", "bf16", 65536, 1024, 1024, "tall-skinny, epilogue-heavy"),
     "cfg3": Workload("cfg3", "bf16", 16, 8192, 8192, "small-M, streams W"),
     "cfg4": Workload("cfg4", "bf16", 8192, 4096, 16384, "wide rows, many N tiles"),
+    "f32_4096": Workload("f32_4096", "f32", 4096, 4096, 4096, "fp32 inputs and outputs at the square shape"),
 }
 
 

@@ -34,6 +34,8 @@ SMALL_CASES = [
     (2085, 264, 4088, "bf16", TWOPASS, TWOPASS),
     (2100, 96, 2048, "f32", AUTO, FUSED),       # fp32 on 256-tiles
     (40, 128, 1024, "bf16", AUTO, FUSED),       # just above the small-M limit
+    (1000, 520, 5004, "f32", AUTO, FUSED),      # fp32, N neither a power of two nor a tile multiple
+    (513, 1028, 1284, "f32", TWOPASS, TWOPASS), # fp32, K with a 4-element tail, two-pass
 ]
 
 
@@ -86,7 +88,7 @@ def test_linear_stage_exact_on_integers(M, K, N, dtype):
 
 
 # ------------------------------------------------- full sizes, sampled rows
-@pytest.mark.parametrize("name", ["cfg1", "cfg2", "cfg3", "cfg4"])
+@pytest.mark.parametrize("name", ["cfg1", "cfg2", "cfg3", "cfg4", "f32_4096"])
 def test_benchmark_sizes_sampled_rows(name):
     """The launch configuration the benchmark times, checked on complete sampled
     rows (LayerNorm needs whole rows): tile-boundary rows plus seeded random rows."""
