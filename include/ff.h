@@ -111,6 +111,36 @@ int ff_cross_entropy_mean(const void *logits, const int64_t *targets, int64_t B,
 size_t ff_cross_entropy_workspace_bytes(int64_t B, int64_t C, int dtype);
 
 /*
+ * Profiling-metric selection (the paper's Sec. 2.3, Steps 2 and 3; Alg. 2).
+ *   values   device, double [n_tasks][n_kernels][n_metrics]: metric m of kernel v of task i.
+ *   runtime  device, double [n_tasks][n_kernels].
+ * Per task, r[i][m] = Pearson correlation over the task's kernels between metric m and the
+ * runtime (NaN when undefined).  If 0 < collinear_tau <= 1, a metric whose |correlation| with an
+ * earlier kept metric of the same task is >= collinear_tau is dropped for that task (needs
+ * n_metrics <= 8192); any other value disables the filter.  Top-k per task by |r| (ties to the
+ * lower index), candidates = union, score[m] = mean over all tasks of |r[i][m]| (NaN counts 0),
+ * *threshold = the given percentile (0..100, linear interpolation) of the candidates' scores,
+ * selected[m] = 1 for candidates in the Top-k of >= min_tasks tasks, with one sign of r over those
+ * tasks and score > *threshold.  The paper uses top_k = 20, percentile = 75, min_tasks = 2.
+ * Outputs are HOST pointers, each optional (NULL): r [n_tasks][n_metrics], score [n_metrics],
+ * top int32 [n_tasks][top_k] (-1 padded), selected uint8 [n_metrics], threshold [1].
+ * The correlations run on the device on `stream`; the call returns after the stream has been
+ * synchronised and the host outputs are complete.  Uses the workspace.  Returns an ff_status.
+ */
+int ff_metric_selection(const double *values, const double *runtime, int64_t n_tasks,
+                        int64_t n_kernels, int64_t n_metrics, int top_k, double percentile,
+                        double collinear_tau, int min_tasks, double *r, double *score,
+                        int32_t *top, uint8_t *selected, double *threshold, void *stream);
+
+/*
+ * The host part of the above on its own (no device is touched): r [n_tasks][n_metrics] and the
+ * optional keep mask uint8 [n_tasks][n_metrics] (NULL = all kept) are host arrays; outputs as above.
+ */
+int ff_metric_select_host(const double *r, const uint8_t *keep, int64_t n_tasks, int64_t n_metrics,
+                          int top_k, double percentile, int min_tasks, int32_t *top, double *score,
+                          uint8_t *selected, double *threshold);
+
+/*
  * Second fused chain, the paper's fused-epilogue case study (App. B.1: Linear ->
  * subtract -> row-mean -> GELU -> residual add):
  *     Out[m][k] = X[m][k] + GELU( mean_n( X[m] . W[n] + b[n] - s[n] ) )

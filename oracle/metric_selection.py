@@ -16,8 +16,8 @@ Step 3 (across tasks).  M* = union of the Top20_i.  Global score S_m = (1/n) sum
 n tasks.  Final = { m in M* : m is in the Top-20 of at least two tasks, r_{m,i} has one sign over
 the tasks whose Top-20 contain m, and S_m > P75 of { S_m : m in M* } }.
 
-Readings where the paper is silent: a correlation with a constant column (or constant runtime) is
-undefined: it is NaN here, never enters a Top-20, and counts as 0 in S_m.  Ties in |r| go to the
+Readings where the paper is silent: a correlation with a constant column (or constant runtime; all
+values equal) is undefined: it is NaN here, never enters a Top-20, and counts as 0 in S_m.  Ties in |r| go to the
 lower metric index.  The percentile interpolates linearly between order statistics (position
 (len - 1) * q / 100 in the sorted list).
 """
@@ -30,12 +30,16 @@ import numpy as np
 
 
 def pearson(x: Sequence[float], y: Sequence[float]) -> float:
-    """r = sum (x - mean x)(y - mean y) / sqrt( sum (x - mean x)^2 * sum (y - mean y)^2 ); NaN if undefined."""
+    """r = sum (x - mean x)(y - mean y) / sqrt( sum (x - mean x)^2 * sum (y - mean y)^2 ).
+    Undefined (NaN) when either sample is constant, i.e. all its values are equal: decided by comparing
+    the values, not by the rounded variance (the mean of equal values need not round to that value)."""
     x = [float(v) for v in x]
     y = [float(v) for v in y]
     n = len(x)
     if n != len(y) or n == 0:
         raise ValueError("two samples of the same positive length")
+    if min(x) == max(x) or min(y) == max(y):
+        return float("nan")
     mx = math.fsum(x) / n
     my = math.fsum(y) / n
     sxy = math.fsum((a - mx) * (b - my) for a, b in zip(x, y))
@@ -96,15 +100,12 @@ def percentile(vals: Sequence[float], q: float) -> float:
     return s[lo] + (pos - lo) * (s[hi] - s[lo])
 
 
-def select(values, runtime, k: int = 20, q: float = 75.0, tau: Optional[float] = None,
-           min_tasks: int = 2) -> Dict[str, object]:
-    values = np.asarray(values, dtype=np.float64)
-    n, V, J = values.shape
-    r = correlations(values, runtime)
-    tops = []
-    for i in range(n):
-        keep = collinear_keep(values[i], tau)
-        tops.append(top_k(list(r[i]), keep, k))
+def select_from_r(r, keeps, k: int = 20, q: float = 75.0, min_tasks: int = 2) -> Dict[str, object]:
+    """Steps after the correlations: r [n][J]; keeps[i][m] says whether metric m survived the
+    duplicate filter in task i."""
+    r = np.asarray(r, dtype=np.float64)
+    n, J = r.shape
+    tops = [top_k(list(r[i]), keeps[i], k) for i in range(n)]
     candidates = sorted(set(m for t in tops for m in t))          # M*
     score = np.zeros(J, dtype=np.float64)                         # S_m, over all n tasks
     for m in range(J):
@@ -118,3 +119,14 @@ def select(values, runtime, k: int = 20, q: float = 75.0, tau: Optional[float] =
             selected.append(m)
     return {"r": r, "top": tops, "candidates": candidates, "score": score, "threshold": threshold,
             "selected": selected}
+
+
+def select(values, runtime, k: int = 20, q: float = 75.0, tau: Optional[float] = None,
+           min_tasks: int = 2) -> Dict[str, object]:
+    values = np.asarray(values, dtype=np.float64)
+    n, V, J = values.shape
+    r = correlations(values, runtime)
+    keeps = [collinear_keep(values[i], tau) for i in range(n)]
+    out = select_from_r(r, keeps, k, q, min_tasks)
+    out["keep"] = keeps
+    return out

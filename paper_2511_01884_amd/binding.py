@@ -19,6 +19,7 @@ FF_VARIANT_AUTO, FF_VARIANT_TILED_FUSED, FF_VARIANT_TILED_TWOPASS, FF_VARIANT_SM
 EXPORTS = [
     "ff_fused_linear_gelu_ln", "ff_fused_linear_sub_rowmean_gelu_residual", "ff_rowmean_workspace_bytes",
     "ff_cross_entropy_mean", "ff_cross_entropy_workspace_bytes",
+    "ff_metric_selection", "ff_metric_select_host",
     "ff_workspace_bytes", "ff_set_workspace", "ff_check_device",
     "ff_status_string", "ff_version", "ff_last_variant", "ff_debug_linear",
     "ff_debug_force_variant", "ff_debug_set_wait_limit_us", "ff_debug_expect_extra_arrivals",
@@ -51,6 +52,11 @@ def load() -> ctypes.CDLL:
         lib.ff_rowmean_workspace_bytes.argtypes = [i64, i64, i64, ci]
         lib.ff_cross_entropy_mean.restype = ci
         lib.ff_cross_entropy_mean.argtypes = [vp, vp, i64, i64, ci, vp, vp, vp]
+        lib.ff_metric_selection.restype = ci
+        lib.ff_metric_selection.argtypes = [vp, vp, i64, i64, i64, ci, ctypes.c_double, ctypes.c_double, ci,
+                                            vp, vp, vp, vp, vp, vp]
+        lib.ff_metric_select_host.restype = ci
+        lib.ff_metric_select_host.argtypes = [vp, vp, i64, i64, ci, ctypes.c_double, ci, vp, vp, vp, vp]
         lib.ff_cross_entropy_workspace_bytes.restype = ctypes.c_size_t
         lib.ff_cross_entropy_workspace_bytes.argtypes = [i64, i64, ci]
         lib.ff_workspace_bytes.restype = ctypes.c_size_t
@@ -231,6 +237,58 @@ def ff_cross_entropy_mean(logits: torch.Tensor, targets: torch.Tensor, row_loss:
 
 def ff_cross_entropy_workspace_bytes(B: int, C: int, dtype: int) -> int:
     return int(load().ff_cross_entropy_workspace_bytes(B, C, dtype))
+
+
+def _selection_outputs(n: int, J: int, k: int):
+    import numpy as np
+    return (np.empty((n, J), dtype=np.float64), np.empty(J, dtype=np.float64),
+            np.empty((n, k), dtype=np.int32), np.empty(J, dtype=np.uint8), np.empty(1, dtype=np.float64))
+
+
+def _selection_result(r, score, top, selected, threshold):
+    return {"r": r, "score": score, "top": [[int(m) for m in row if m >= 0] for row in top],
+            "selected": [int(m) for m in selected.nonzero()[0]], "threshold": float(threshold[0])}
+
+
+def ff_metric_selection(values: torch.Tensor, runtime: torch.Tensor, top_k: int = 20, percentile: float = 75.0,
+                        collinear_tau: float = 0.0, min_tasks: int = 2, stream=None):
+    """Metric selection on device arrays values [n,V,J] and runtime [n,V] (float64); returns a dict of
+    host results: r, score, top (lists of metric indices), selected (indices), threshold."""
+    if values.dim() != 3 or runtime.dim() != 2 or tuple(runtime.shape) != tuple(values.shape[:2]):
+        raise ValueError("values must be [n,V,J] and runtime [n,V]")
+    if values.dtype != torch.float64 or runtime.dtype != torch.float64:
+        raise TypeError("values and runtime must be float64")
+    for t in (values, runtime):
+        if not t.is_cuda or not t.is_contiguous() or t.device != values.device:
+            raise ValueError("values and runtime must be contiguous tensors on one device")
+    n, V, J = values.shape
+    r, score, top, selected, threshold = _selection_outputs(n, J, int(top_k))
+    with torch.cuda.device(values.device):
+        rc = load().ff_metric_selection(
+            ctypes.c_void_p(values.data_ptr()), ctypes.c_void_p(runtime.data_ptr()), n, V, J, int(top_k),
+            float(percentile), float(collinear_tau), int(min_tasks), r.ctypes.data, score.ctypes.data,
+            top.ctypes.data, selected.ctypes.data, threshold.ctypes.data, _stream(stream))
+    if rc != FF_OK:
+        raise FFError(rc)
+    return _selection_result(r, score, top, selected, threshold)
+
+
+def ff_metric_select_host(r, keep=None, top_k: int = 20, percentile: float = 75.0, min_tasks: int = 2):
+    """The host part alone: r [n,J] float64 numpy, keep [n,J] uint8 numpy or None."""
+    import numpy as np
+    r = np.ascontiguousarray(r, dtype=np.float64)
+    n, J = r.shape
+    if keep is not None:
+        keep = np.ascontiguousarray(keep, dtype=np.uint8)
+        if keep.shape != r.shape:
+            raise ValueError("keep must have the shape of r")
+    _, score, top, selected, threshold = _selection_outputs(n, J, int(top_k))
+    rc = load().ff_metric_select_host(r.ctypes.data, None if keep is None else keep.ctypes.data, n, J, int(top_k),
+                                      float(percentile), int(min_tasks), top.ctypes.data, score.ctypes.data,
+                                      selected.ctypes.data, threshold.ctypes.data)
+    if rc != FF_OK:
+        raise FFError(rc)
+    return _selection_result(r, score, top, selected, threshold)
 
 
 def ff_debug_linear(X: torch.Tensor, W: torch.Tensor, b: Optional[torch.Tensor],

@@ -2,6 +2,8 @@
 // selection by shape, workspace management and kernel launches.  Nothing here
 // computes on tensors and nothing falls back to a library GEMM or LayerNorm.
 #include <mutex>
+#include <vector>
+#include <algorithm>
 
 #include "../../include/ff.h"
 #include "ff_tile.hpp"
@@ -405,6 +407,83 @@ size_t ff_cross_entropy_workspace_bytes(int64_t B, int64_t C, int dtype)
         return 0;
     // sized for the largest grid any device uses here (8 workgroups per compute unit, 1024 units)
     return kCtrlBytes + 8192 * sizeof(floatx2);
+}
+
+int ff_metric_select_host(const double *r, const uint8_t *keep, int64_t n_tasks, int64_t n_metrics,
+                          int top_k, double percentile, int min_tasks, int32_t *top, double *score,
+                          uint8_t *selected, double *threshold)
+{
+    if (!r)
+        return FF_ERR_NULL;
+    if (n_tasks <= 0 || n_metrics <= 0 || top_k <= 0 || n_tasks > 1 << 20 || n_metrics > 1 << 24 ||
+        !(percentile >= 0.0 && percentile <= 100.0) || min_tasks < 1)
+        return FF_ERR_SHAPE;
+    metric_select_host(r, keep, (int)n_tasks, (int)n_metrics, top_k, percentile, min_tasks, top, score,
+                       selected, threshold);
+    return FF_OK;
+}
+
+int ff_metric_selection(const double *values, const double *runtime, int64_t n_tasks, int64_t n_kernels,
+                        int64_t n_metrics, int top_k, double percentile, double collinear_tau,
+                        int min_tasks, double *r_host, double *score_host, int32_t *top_host,
+                        uint8_t *selected_host, double *threshold_host, void *stream)
+{
+    if (!values || !runtime)
+        return FF_ERR_NULL;
+    if (n_tasks <= 0 || n_kernels <= 0 || n_metrics <= 0 || top_k <= 0 || n_tasks > 1 << 16 ||
+        n_kernels > 1 << 20 || n_metrics > 1 << 24 || !(percentile >= 0.0 && percentile <= 100.0) ||
+        min_tasks < 1)
+        return FF_ERR_SHAPE;
+    const bool filter = collinear_tau > 0.0 && collinear_tau <= 1.0;
+    if (filter && n_metrics > 8192)
+        return FF_ERR_UNSUPPORTED;  // the J x J correlation matrix of a task is held in the workspace
+    if ((reinterpret_cast<uintptr_t>(values) & 7u) || (reinterpret_cast<uintptr_t>(runtime) & 7u))
+        return FF_ERR_ALIGN;
+    const int n = (int)n_tasks, V = (int)n_kernels, J = (int)n_metrics;
+    hipStream_t st_stream = static_cast<hipStream_t>(stream);
+    std::vector<double> r((size_t)n * J);
+    std::vector<uint8_t> keep;
+    {
+        std::lock_guard<std::mutex> lock(g_mutex);
+        DeviceState *st = current_device_state();
+        if (!st)
+            return FF_ERR_LAUNCH;
+        const size_t r_bytes = round_up((size_t)n * J * sizeof(double), 256);
+        const size_t z_bytes = filter ? round_up((size_t)V * J * sizeof(double), 256) : 0;
+        const size_t c_bytes = filter ? round_up((size_t)J * J * sizeof(double), 256) : 0;
+        const int rc = prepare_workspace(*st, kCtrlBytes + r_bytes + z_bytes + c_bytes, st_stream);
+        if (rc != FF_OK)
+            return rc;
+        char *ws = static_cast<char *>(st->ws);
+        double *r_dev = reinterpret_cast<double *>(ws + kCtrlBytes);
+        double *z_dev = reinterpret_cast<double *>(ws + kCtrlBytes + r_bytes);
+        double *c_dev = reinterpret_cast<double *>(ws + kCtrlBytes + r_bytes + z_bytes);
+        if (launch_pearson(values, runtime, r_dev, n, V, J, st_stream) != hipSuccess)
+            return FF_ERR_LAUNCH;
+        if (hipMemcpyAsync(r.data(), r_dev, (size_t)n * J * sizeof(double), hipMemcpyDeviceToHost, st_stream) !=
+            hipSuccess)
+            return FF_ERR_LAUNCH;
+        if (filter) {
+            keep.resize((size_t)n * J);
+            std::vector<double> C((size_t)J * J);
+            for (int i = 0; i < n; ++i) {
+                if (launch_corr_matrix(values + (size_t)i * V * J, z_dev, c_dev, V, J, st_stream) != hipSuccess)
+                    return FF_ERR_LAUNCH;
+                if (hipMemcpyAsync(C.data(), c_dev, (size_t)J * J * sizeof(double), hipMemcpyDeviceToHost,
+                                   st_stream) != hipSuccess ||
+                    hipStreamSynchronize(st_stream) != hipSuccess)
+                    return FF_ERR_LAUNCH;
+                metric_greedy_keep(C.data(), J, collinear_tau, keep.data() + (size_t)i * J);
+            }
+        }
+        if (hipStreamSynchronize(st_stream) != hipSuccess)
+            return FF_ERR_LAUNCH;
+    }
+    metric_select_host(r.data(), filter ? keep.data() : nullptr, n, J, top_k, percentile, min_tasks, top_host,
+                       score_host, selected_host, threshold_host);
+    if (r_host)
+        std::copy(r.begin(), r.end(), r_host);
+    return FF_OK;
 }
 
 size_t ff_workspace_bytes(int64_t M, int64_t K, int64_t N, int dtype)

@@ -79,6 +79,14 @@ struct XentParams {
     int wg_per_row;            // 1: a workgroup per row (long rows, few rows); 0: a wavefront per row
 };
 
+// profiling-metric selection: device correlations, host selection
+hipError_t launch_pearson(const double *values, const double *runtime, double *r, int n, int V, int J,
+                          hipStream_t stream);
+hipError_t launch_corr_matrix(const double *task_values, double *Z, double *C, int V, int J, hipStream_t stream);
+void metric_greedy_keep(const double *C, int J, double tau, unsigned char *keep);
+void metric_select_host(const double *r, const unsigned char *keep, int n, int J, int k, double q,
+                        int min_tasks, int *top, double *score, unsigned char *selected, double *threshold);
+
 hipError_t launch_xent_kernel(bool bf16, const XentParams &p, hipStream_t stream);
 hipError_t launch_rowmean_chain(bool bf16, const RowMeanParams &p, hipStream_t stream);
 hipError_t launch_tile_kernel(bool bf16, int tile, int mode, const TileParams &p, int grid,

@@ -102,6 +102,33 @@ def make_xent_inputs(B: int, C: int, dtype: str = "f32", seed: int = 0, scale: f
     return logits, targets
 
 
+def make_metric_inputs(n: int, V: int, J: int, seed: int = 0):
+    """Synthetic profile dumps for the metric-selection procedure (Sec. 2.3): n tasks, V kernels per
+    task, J metrics.  runtime[i][v] is log-normal; metric m follows the runtime with a per-metric
+    strength in [-1, 1] (jittered per task, so some metrics flip sign or fade between tasks) plus
+    noise, at counter-like magnitudes from 1 to 1e9; every 17th metric is constant, every 19th is an
+    exact copy of its left neighbour, every 23rd an affine image of it.  float64 tensors
+    values [n,V,J], runtime [n,V]."""
+    g = torch.Generator(device="cpu").manual_seed(seed)
+    runtime = torch.exp(0.5 * torch.randn(n, V, generator=g, dtype=torch.float64))
+    z = (runtime - runtime.mean(dim=1, keepdim=True)) / runtime.std(dim=1, keepdim=True, unbiased=False).clamp_min(1e-30)
+    strength = torch.rand(J, generator=g, dtype=torch.float64) * 2 - 1
+    jitter = 0.5 * torch.randn(n, J, generator=g, dtype=torch.float64)
+    a = (strength[None, :] + jitter).clamp(-1, 1)
+    noise = torch.randn(n, V, J, generator=g, dtype=torch.float64)
+    scale = torch.pow(10.0, torch.rand(J, generator=g, dtype=torch.float64) * 9)
+    offset = scale * (torch.rand(J, generator=g, dtype=torch.float64) * 4)
+    values = scale * (a[:, None, :] * z[:, :, None] + torch.sqrt(1 - a * a)[:, None, :] * noise) + offset
+    for m in range(J):
+        if m % 17 == 16:
+            values[:, :, m] = offset[m]
+        elif m % 19 == 18 and m > 0:
+            values[:, :, m] = values[:, :, m - 1]
+        elif m % 23 == 22 and m > 0:
+            values[:, :, m] = 3.0 * values[:, :, m - 1] + 1.0
+    return values.contiguous(), runtime.contiguous()
+
+
 def sample_rows(M: int, n: int, tile: int = 256, seed: int = 0):
     """Row indices for sampled checks at full size: the rows next to tile
     boundaries plus seeded random rows, sorted and unique."""

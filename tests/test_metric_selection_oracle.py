@@ -30,6 +30,12 @@ def pin_pearson_textbook(m):
     assert abs(m.pearson([0, 1, 2, 3], [5, 3, 1, -1]) + 1.0) < 1e-15          # exact line, negative slope
     assert abs(m.pearson([0, 1, 2, 3], [1, 1.5, 2, 2.5]) - 1.0) < 1e-15
     assert math.isnan(m.pearson([2, 2, 2], [1, 2, 3])) and math.isnan(m.pearson([1, 2, 3], [7, 7, 7]))
+    # ten equal values whose mean does not round back to the value: still a constant column
+    for n_, const in ((3, 763774.6425991522), (6, 721540.0601867794), (7, 228762.29839423054),
+                      (10, 945270.7010268527)):
+        assert math.fsum([const] * n_) / n_ != const          # why the variance is no test for constancy
+        assert math.isnan(m.pearson([const] * n_, list(range(n_)))), const
+        assert math.isnan(m.pearson(list(range(n_)), [const] * n_)), const
     rng = np.random.default_rng(3)
     for _ in range(20):
         x, y = rng.normal(size=10) * 1e3 + 5e4, rng.normal(size=10)
@@ -188,6 +194,7 @@ def test_pin(pin):
 MUTANTS = [
     ("covariance_not_centred", "sxy = math.fsum((a - mx) * (b - my) for a, b in zip(x, y))",
      "sxy = math.fsum(a * b for a, b in zip(x, y))"),
+    ("constant_by_variance", "    if min(x) == max(x) or min(y) == max(y):\n        return float(\"nan\")\n", ""),
     ("no_square_root", "return sxy / math.sqrt(sxx * syy)", "return sxy / (sxx * syy)"),
     ("divides_by_sxx_only", "return sxy / math.sqrt(sxx * syy)", "return sxy / sxx"),
     ("top_by_signed_r", "cand.sort(key=lambda m: (-abs(r_task[m]), m))", "cand.sort(key=lambda m: (-r_task[m], m))"),
