@@ -207,6 +207,13 @@ int ff_debug_linear(const void *X, const void *W, const void *b,
  * FF_ERR_UNSUPPORTED; it never silently runs something else. */
 int ff_debug_force_variant(int variant);
 
+/* Tile shape of the tiled variants for later calls: tile = 0 (automatic), 128 or 256;
+ * wg_per_cu = 0 or 1 (a persistent grid of one workgroup per compute unit) or 2 (two, with
+ * 128-tiles only).  The automatic choice is the fastest on every measured shape; the other
+ * shapes exist as distinct kernels of the same operator for the profiling-metric study and
+ * for tests.  FF_ERR_UNSUPPORTED for any other combination. */
+int ff_debug_force_tile(int tile, int wg_per_cu);
+
 /* Upper bound, in microseconds, a workgroup waits for the other tiles of its
  * rows before it gives up and flags FF_ERR_DEVICE (default 2,000,000). */
 int ff_debug_set_wait_limit_us(int64_t microseconds);

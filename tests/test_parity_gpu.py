@@ -49,6 +49,26 @@ def test_full_matrix_parity(M, K, N, dtype, variant, expect):
     print(stats)
 
 
+@pytest.mark.parametrize("tile,per_cu", [(128, 1), (128, 2), (256, 1)])
+@pytest.mark.parametrize("variant", [FUSED, TWOPASS])
+def test_forced_tile_shapes_parity(tile, per_cu, variant):
+    """The tile shapes the automatic plan does not pick for this size are kernels of the same
+    operator (used as distinct variants by the profiling-metric study): same gates."""
+    _announce("forced tile", tile, per_cu, variant)
+    d = make_inputs(1300, 520, 2056, "bf16", seed=14)
+    B.ff_debug_force_tile(tile, per_cu)
+    try:
+        Y, used = gpu_run(d, variant)
+    finally:
+        B.ff_debug_force_tile(0, 0)
+    assert used == variant
+    print(check_against_oracle(Y, oracle_on(d), "bf16", "tile %d x%d" % (tile, per_cu)))
+    with pytest.raises(B.FFError):
+        B.ff_debug_force_tile(256, 2)
+    with pytest.raises(B.FFError):
+        B.ff_debug_force_tile(64, 1)
+
+
 SMALLM_CASES = [(16, 8192, 8192), (16, 1024, 1024), (5, 520, 1000), (32, 1024, 2048),
                 (17, 72, 40), (1, 8, 8), (16, 4096, 32768), (9, 256, 16384 + 64)]
 
