@@ -27,27 +27,33 @@ PEAK_HBM_GBS = 8000.0
 INFINITY_CACHE_BYTES = 256 << 20
 
 # HBM traffic per launch of the dominant kernel, from two `rocprofv3 --pmc` runs (FETCH_SIZE, then
-# WRITE_SIZE, KiB per dispatch), each scaled by what the same counter reads for a plain copy kernel
-# of 256 MiB (FETCH_SIZE reads 131080 for 262144 KiB -> factor 2.0; WRITE_SIZE 262140 -> 1.0).
-# Valid only for the kernel sources they were taken with: reported as null once the hash differs.
+# WRITE_SIZE, KiB per dispatch), each scaled by what the same counter reads for the library's plain
+# copy kernel on 256 MiB (`--workload copy`): FETCH_SIZE reads 131080 for 262144 KiB -> factor 2.0;
+# WRITE_SIZE 262140 -> 1.0.  An entry is valid only for the device sources of its kernel as they were
+# when the counters were taken: `traffic` is null once their hash differs.
+COMMON_SOURCES = ["ff_device.hpp", "ff_tile.hpp"]
 TRAFFIC = {
-    "source_sha256": "9a4c5e8100bb16e4279df82c9947d275a7013764583afb932ec1b94000bc417e",
-    "bytes": {
-        "cfg1": int((103080 * 2.0 + 44561 * 1.0) * 1024),
-        "cfg3": int((66824 * 2.0 + 336 * 1.0) * 1024),
-    },
+    "cfg1": {"sources": ["ff_tile.hip"], "sha256": "", "bytes": 0},
+    "cfg3": {"sources": ["ff_smallm.hip"], "sha256": "", "bytes": 0},
+    "xent": {"sources": ["ff_xent.hip"], "sha256": "", "bytes": 0},
+    "rowmean": {"sources": ["ff_rowmean.hip"], "sha256": "", "bytes": 0},
 }
 
 
-def kernel_source_hash() -> str:
-    import glob
+def kernel_source_hash(workload: str) -> str:
     import hashlib
     h = hashlib.sha256()
-    for f in sorted(glob.glob(os.path.join(ROOT, "paper_2511_01884_amd", "csrc", "*"))):
-        h.update(os.path.basename(f).encode())
-        h.update(open(f, "rb").read())
+    for name in sorted(TRAFFIC[workload]["sources"] + COMMON_SOURCES):
+        h.update(name.encode())
+        h.update(open(os.path.join(ROOT, "paper_2511_01884_amd", "csrc", name), "rb").read())
     return h.hexdigest()
 
+
+def measured_traffic(workload: str):
+    t = TRAFFIC.get(workload)
+    if t is None or not t["sha256"] or t["sha256"] != kernel_source_hash(workload):
+        return None
+    return t["bytes"]
 
 
 def algorithmic_bytes(M, K, N, esize):
@@ -70,7 +76,8 @@ def main() -> int:
     ap.add_argument("--print-source-hash", action="store_true", help="print the kernel source hash and exit")
     args = ap.parse_args()
     if args.print_source_hash:
-        print(kernel_source_hash())
+        for w in TRAFFIC:
+            print(w, kernel_source_hash(w))
         return 0
 
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
@@ -92,6 +99,8 @@ def main() -> int:
         return bench_rowmean(args, torch, B)
     if args.workload == "xent":
         return bench_xent(args, torch, B)
+    if args.workload == "copy":
+        return bench_copy(args, torch, B)
     wl = CONFIGS[args.workload]
     M, K, N = wl.M, wl.K, wl.N
     esize = 4 if wl.dtype == "f32" else 2
@@ -146,8 +155,7 @@ def main() -> int:
         roof = {"bound": "mfma", "achieved": flops / (ms_kernel * 1e-3) / 1e12, "peak": peak,
                 "unit": "TFLOP/s"}
     roof["frac"] = roof["achieved"] / roof["peak"]
-    roof["traffic"] = (TRAFFIC["bytes"].get(args.workload)
-                       if TRAFFIC["source_sha256"] == kernel_source_hash() else None)
+    roof["traffic"] = measured_traffic(args.workload)
     roof["kernel_ms"] = ms_kernel
 
     out = {
@@ -250,8 +258,9 @@ def bench_rowmean(args, torch, B) -> int:
                    "buffer_sets": n_sets, "algorithmic_mb_per_step": abytes / 1e6,
                    "note": "three launches per step (column sums, column means, row pass)"},
         "roofline": {"bound": "hbm", "achieved": abytes / (ms_kernel * 1e-3) / 1e9, "peak": PEAK_HBM_GBS,
-                     "unit": "GB/s", "frac": abytes / (ms_kernel * 1e-3) / 1e9 / PEAK_HBM_GBS, "traffic": None,
-                     "kernel_ms": ms_kernel},
+                     "unit": "GB/s", "frac": abytes / (ms_kernel * 1e-3) / 1e9 / PEAK_HBM_GBS,
+                     "traffic": measured_traffic("rowmean"), "kernel_ms": ms_kernel,
+                     "note": "rate over all three kernels of the chain; traffic is the three kernels' sum"},
     }
     if not args.no_eager:
         def eager(i):
@@ -284,6 +293,30 @@ def bench_rowmean(args, torch, B) -> int:
                                "sample": "%d of %d rows in %.1f s (the oracle evaluates the full linear layer per row); "
                                          "rate scaled to the full matrix" % (n_rows, M, c_s)}
     print(json.dumps(out))
+    return 0
+
+
+def bench_copy(args, torch, B) -> int:
+    """The library's plain copy kernel on 256 MiB: the kernel of known traffic that scales the byte counters."""
+    nbytes = 256 << 20
+    src = torch.empty(nbytes, dtype=torch.uint8, device="cuda").random_(0, 255)
+    dst = torch.empty_like(src)
+    for _ in range(args.warmup):
+        B.ff_debug_copy(src, dst)
+    torch.cuda.synchronize()
+    ev0 = torch.cuda.Event(enable_timing=True)
+    ev1 = torch.cuda.Event(enable_timing=True)
+    ev0.record()
+    for _ in range(args.steps):
+        B.ff_debug_copy(src, dst)
+    ev1.record()
+    torch.cuda.synchronize()
+    assert torch.equal(src, dst)
+    ms = ev0.elapsed_time(ev1) / args.steps
+    print(json.dumps({"metric": "copy kernel, bytes read + written per second", "value": 2 * nbytes / (ms * 1e-3) / 1e9,
+                      "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms,
+                      "higher_is_better": True, "dtype": "u8", "data": "synthetic",
+                      "config": {"workload": "copy: 256 MiB device-to-device, counter calibration"}}))
     return 0
 
 
@@ -324,8 +357,8 @@ def bench_xent(args, torch, B) -> int:
         "config": {"workload": "xent: row-wise cross-entropy with mean, fp32 logits [32768, 4096], int64 targets",
                    "buffer_sets": n_sets, "algorithmic_mb_per_step": abytes / 1e6},
         "roofline": {"bound": "hbm", "achieved": abytes / (ms_kernel * 1e-3) / 1e9, "peak": PEAK_HBM_GBS,
-                     "unit": "GB/s", "frac": abytes / (ms_kernel * 1e-3) / 1e9 / PEAK_HBM_GBS, "traffic": None,
-                     "kernel_ms": ms_kernel},
+                     "unit": "GB/s", "frac": abytes / (ms_kernel * 1e-3) / 1e9 / PEAK_HBM_GBS,
+                     "traffic": measured_traffic("xent"), "kernel_ms": ms_kernel},
     }
     if not args.no_eager:
         def eager(i):

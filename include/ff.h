@@ -207,6 +207,11 @@ int ff_debug_linear(const void *X, const void *W, const void *b,
  * FF_ERR_UNSUPPORTED; it never silently runs something else. */
 int ff_debug_force_variant(int variant);
 
+/* Plain device-to-device copy of `bytes` (a multiple of 16; both pointers 16-byte aligned, device,
+ * not overlapping) on `stream`.  A kernel of exactly known HBM traffic, used to scale hardware byte
+ * counters when the traffic of the other kernels is measured. */
+int ff_debug_copy(const void *src, void *dst, size_t bytes, void *stream);
+
 /* Tile shape of the tiled variants for later calls: tile = 0 (automatic), 128 or 256;
  * wg_per_cu = 0 or 1 (a persistent grid of one workgroup per compute unit) or 2 (two, with
  * 128-tiles only).  The automatic choice is the fastest on every measured shape; the other

@@ -22,7 +22,7 @@ EXPORTS = [
     "ff_metric_selection", "ff_metric_select_host",
     "ff_workspace_bytes", "ff_set_workspace", "ff_check_device",
     "ff_status_string", "ff_version", "ff_last_variant", "ff_debug_linear",
-    "ff_debug_force_variant", "ff_debug_force_tile", "ff_debug_set_wait_limit_us", "ff_debug_expect_extra_arrivals",
+    "ff_debug_force_variant", "ff_debug_force_tile", "ff_debug_copy", "ff_debug_set_wait_limit_us", "ff_debug_expect_extra_arrivals",
 ]
 
 _lib = None
@@ -73,6 +73,8 @@ def load() -> ctypes.CDLL:
         lib.ff_debug_linear.argtypes = [vp, vp, vp, i64, i64, i64, ci, vp, vp]
         lib.ff_debug_force_variant.restype = ci
         lib.ff_debug_force_variant.argtypes = [ci]
+        lib.ff_debug_copy.restype = ci
+        lib.ff_debug_copy.argtypes = [vp, vp, ctypes.c_size_t, vp]
         lib.ff_debug_force_tile.restype = ci
         lib.ff_debug_force_tile.argtypes = [ci, ci]
         lib.ff_debug_set_wait_limit_us.restype = ci
@@ -140,6 +142,17 @@ def ff_check_device(stream=None) -> None:
 
 def ff_debug_force_variant(variant: int) -> None:
     rc = load().ff_debug_force_variant(int(variant))
+    if rc != FF_OK:
+        raise FFError(rc)
+
+
+def ff_debug_copy(src: torch.Tensor, dst: torch.Tensor, stream=None) -> None:
+    """dst <- src with the library's plain copy kernel (counter calibration)."""
+    nbytes = src.numel() * src.element_size()
+    if dst.numel() * dst.element_size() != nbytes:
+        raise ValueError("src and dst must have the same size in bytes")
+    with torch.cuda.device(src.device):
+        rc = load().ff_debug_copy(_ptr(src), _ptr(dst), nbytes, _stream(stream))
     if rc != FF_OK:
         raise FFError(rc)
 

@@ -592,6 +592,22 @@ int ff_debug_force_tile(int tile, int wg_per_cu)
     return FF_OK;
 }
 
+int ff_debug_copy(const void *src, void *dst, size_t bytes, void *stream)
+{
+    if (!src || !dst)
+        return FF_ERR_NULL;
+    if (misaligned(src) || misaligned(dst))
+        return FF_ERR_ALIGN;
+    if (bytes % 16 != 0)
+        return FF_ERR_UNSUPPORTED;
+    DeviceState *st = current_device_state();
+    if (!st)
+        return FF_ERR_LAUNCH;
+    if (launch_copy_kernel(src, dst, bytes, st->num_cus, static_cast<hipStream_t>(stream)) != hipSuccess)
+        return FF_ERR_LAUNCH;
+    return FF_OK;
+}
+
 int ff_debug_expect_extra_arrivals(int count)
 {
     if (count < 0 || count > 1024)

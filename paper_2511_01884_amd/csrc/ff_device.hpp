@@ -143,4 +143,37 @@ __device__ __forceinline__ bool wait_counter(const unsigned *counter, unsigned t
     }
 }
 
+// Grid-wide arrival spread over several counters.  A few hundred workgroups bumping and polling one
+// word queue up behind each other at the memory side; with kSyncWays words on different
+// 4 KiB pages the queues are kSyncWays times shorter.  Way w of the control region's counter
+// array: arrivals at [w * kSyncStride], departures at [w * kSyncStride + 1]; word [2] counts the
+// ways whose workgroups have all departed.
+constexpr int kSyncWays = 32;
+constexpr int kSyncStride = 1024;  // uint32 words between ways
+
+// Called by every lane of one wavefront; lane l < kSyncWays polls way l until it has seen
+// `target` arrivals there (sticky: a way counts once seen).  False if the bound expired.
+__device__ __forceinline__ bool wait_counters_wave(const unsigned *counters, unsigned target,
+                                                   long long limit_ticks)
+{
+    const int lane = threadIdx.x & 63;
+    const bool polls = lane < kSyncWays;
+    const unsigned *mine = counters + (size_t)(polls ? lane : 0) * kSyncStride;
+    bool seen = !polls || atomic_load_device(mine) >= target;
+    if (__all(seen))
+        return true;
+    const long long t0 = wall_clock64();
+    for (;;) {
+        for (int i = 0; i < 256; ++i) {
+            __builtin_amdgcn_s_sleep(1);
+            if (!seen)
+                seen = atomic_load_device(mine) >= target;
+            if (__all(seen))
+                return true;
+        }
+        if (wall_clock64() - t0 > limit_ticks)
+            return false;
+    }
+}
+
 }  // namespace ff

@@ -250,9 +250,14 @@ __global__ __launch_bounds__(kThreads) void smallm_kernel(const SmallMParams p)
     // ---- exchange the strip statistics across the whole grid ----
     wait_published();
     __syncthreads();
-    if (tid == 0) {
-        atomic_add_device(p.counters, 1u);
-        if (!wait_counter(p.counters, gridDim.x + (unsigned)p.extra_arrivals, p.wait_ticks))
+    const int way = blockIdx.x % kSyncWays;
+    if (tid == 0)
+        atomic_add_device(p.counters + (size_t)way * kSyncStride, 1u);
+    if (wave == 0) {
+        // lane l polls way l: workgroups l, l + kSyncWays, ... arrive there
+        const int l = lane < kSyncWays ? lane : 0;
+        const unsigned target = (gridDim.x + kSyncWays - 1 - l) / kSyncWays + (l == 0 ? (unsigned)p.extra_arrivals : 0u);
+        if (!wait_counters_wave(p.counters, target, p.wait_ticks) && lane == 0)
             atomic_store_device(p.err, 1u);
     }
     __syncthreads();
@@ -319,13 +324,6 @@ __global__ __launch_bounds__(kThreads) void smallm_kernel(const SmallMParams p)
         }
         __syncthreads();
     }
-    if (tid == 0) {
-        if (atomic_add_device(p.counters + 1, 1u) == gridDim.x - 1u) {
-            atomic_store_device(p.counters, 0u);
-            atomic_store_device(p.counters + 1, 0u);
-        }
-    }
-
     // ---- normalise and store ----
     owned = 0;
     for (int strip = blockIdx.x; strip < p.strips; strip += gridDim.x, ++owned) {
@@ -353,6 +351,22 @@ __global__ __launch_bounds__(kThreads) void smallm_kernel(const SmallMParams p)
                 // even lanes store two adjacent bf16 values (N is a multiple of 8)
                 if ((tid & 1) == 0)
                     reinterpret_cast<unsigned *>(p.Y)[((size_t)m * N + n) >> 1] = pack_bf16x2(y, y_other);
+            }
+        }
+    }
+
+    // ---- departure: the last workgroup of the last way re-arms every counter ----
+    // (only then has every workgroup left its wait, so no poller can see a counter go back to zero)
+    if (tid == 0) {
+        const unsigned in_way = (gridDim.x + kSyncWays - 1 - way) / kSyncWays;
+        const unsigned ways = gridDim.x < (unsigned)kSyncWays ? gridDim.x : (unsigned)kSyncWays;
+        if (atomic_add_device(p.counters + (size_t)way * kSyncStride + 1, 1u) == in_way - 1u) {
+            if (atomic_add_device(p.counters + 2, 1u) == ways - 1u) {
+                for (int w = 0; w < kSyncWays; ++w) {
+                    atomic_store_device(p.counters + (size_t)w * kSyncStride, 0u);
+                    atomic_store_device(p.counters + (size_t)w * kSyncStride + 1, 0u);
+                }
+                atomic_store_device(p.counters + 2, 0u);
             }
         }
     }

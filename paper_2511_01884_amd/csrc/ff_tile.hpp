@@ -79,6 +79,8 @@ struct XentParams {
     int wg_per_row;            // 1: a workgroup per row (long rows, few rows); 0: a wavefront per row
 };
 
+hipError_t launch_copy_kernel(const void *src, void *dst, size_t bytes, int num_cus, hipStream_t stream);
+
 // profiling-metric selection: device correlations, host selection
 hipError_t launch_pearson(const double *values, const double *runtime, double *r, int n, int V, int J,
                           hipStream_t stream);
