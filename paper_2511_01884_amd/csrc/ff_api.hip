@@ -288,11 +288,12 @@ int ff_debug_linear(const void *X, const void *W, const void *b, int64_t M, int6
 
 namespace {
 
-// Row chunks of the column-sum kernel: enough workgroups to keep HBM busy.
-void rowmean_plan(int64_t K, int64_t N, int dtype, int &chunks, int &rows_per_chunk)
+// Column strips and row chunks of the second chain's first phase: about one (strip, chunk) item per
+// compute unit of the part this was tuned on; the kernel loops when there are more items than workgroups.
+void rowmean_plan(int64_t K, int64_t N, int dtype, int &strips, int &chunks, int &rows_per_chunk)
 {
-    const int64_t per_strip = 128 * (dtype == FF_BF16 ? 8 : 4);
-    const int64_t strips = (K + per_strip - 1) / per_strip;
+    const int64_t per_strip = kRowMeanColThreads * (dtype == FF_BF16 ? 8 : 4);
+    strips = (int)((K + per_strip - 1) / per_strip);
     int64_t want = 256 / strips;
     if (want < 1)
         want = 1;
@@ -324,7 +325,7 @@ int ff_fused_linear_sub_rowmean_gelu_residual(const void *X, const void *W, cons
     if (!st)
         return FF_ERR_LAUNCH;
     RowMeanParams p{};
-    rowmean_plan(K, N, dtype, p.chunks, p.rows_per_chunk);
+    rowmean_plan(K, N, dtype, p.strips, p.chunks, p.rows_per_chunk);
     const size_t partial_bytes = round_up((size_t)p.chunks * (size_t)K * sizeof(float), 256);
     const size_t wbar_bytes = round_up((size_t)(K + 1) * sizeof(float), 256);
     rc = prepare_workspace(*st, kCtrlBytes + partial_bytes + wbar_bytes, static_cast<hipStream_t>(stream));
@@ -334,10 +335,12 @@ int ff_fused_linear_sub_rowmean_gelu_residual(const void *X, const void *W, cons
     p.X = X; p.W = W; p.b = b; p.s = s; p.Out = Out;
     p.partial = reinterpret_cast<float *>(ws + kCtrlBytes);
     p.wbar = reinterpret_cast<float *>(ws + kCtrlBytes + partial_bytes);
+    p.counters = reinterpret_cast<unsigned *>(ws + kCounterOffset);
+    p.err = reinterpret_cast<unsigned *>(ws);
     p.M = (int)M; p.K = (int)K; p.N = (int)N;
-    const int64_t groups = (M + kRowMeanWaves - 1) / kRowMeanWaves;
-    const int64_t cap = (int64_t)st->num_cus * 4;
-    p.row_grid = (int)(groups < cap ? groups : cap);
+    p.grid = st->num_cus;  // one workgroup per compute unit, all resident: the phases meet inside the launch
+    p.extra_arrivals = g_extra_arrivals;
+    p.wait_ticks = g_wait_limit_us * st->ticks_per_us;
     if (launch_rowmean_chain(dtype == FF_BF16, p, static_cast<hipStream_t>(stream)) != hipSuccess)
         return FF_ERR_LAUNCH;
     return FF_OK;
@@ -349,8 +352,8 @@ namespace {
 
 size_t rowmean_workspace_bytes(int64_t K, int64_t N, int dtype)
 {
-    int chunks, rpc;
-    rowmean_plan(K, N, dtype, chunks, rpc);
+    int strips, chunks, rpc;
+    rowmean_plan(K, N, dtype, strips, chunks, rpc);
     return kCtrlBytes + round_up((size_t)chunks * (size_t)K * sizeof(float), 256) +
            round_up((size_t)(K + 1) * sizeof(float), 256);
 }

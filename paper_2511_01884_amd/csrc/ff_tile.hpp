@@ -52,9 +52,8 @@ struct SmallMParams {
     long long wait_ticks;
 };
 
-// wavefronts (one row each) per workgroup of the row pass of the second chain
-constexpr int kRowMeanWaves = 8;
-// row groups per workgroup of its column-sum pass: rows_per_chunk is a multiple of 8 times this
+// second chain: a workgroup is kRowMeanColSub row groups of kRowMeanColThreads column threads
+constexpr int kRowMeanColThreads = 128;
 constexpr int kRowMeanColSub = 4;
 
 struct RowMeanParams {
@@ -62,9 +61,14 @@ struct RowMeanParams {
     void *Out;
     float *partial;      // [chunks][K] partial column sums of W
     float *wbar;         // [K + 1]: column means of W, then c = mean(b - s)
+    unsigned *counters;  // control-region counter array (zero before and after a launch)
+    unsigned *err;
     int M, K, N;
-    int chunks, rows_per_chunk;
-    int row_grid;
+    int strips;          // column strips of kRowMeanColThreads * (16 / sizeof T) columns
+    int chunks, rows_per_chunk;  // row chunks of W; rows_per_chunk is a multiple of 8 * kRowMeanColSub
+    int grid;            // one workgroup per compute unit: all co-resident
+    int extra_arrivals;  // test hook
+    long long wait_ticks;
 };
 
 struct XentParams {
