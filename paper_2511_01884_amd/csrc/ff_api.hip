@@ -288,18 +288,29 @@ int ff_debug_linear(const void *X, const void *W, const void *b, int64_t M, int6
 
 namespace {
 
-// Column strips and row chunks of the second chain's first phase: about one (strip, chunk) item per
-// compute unit of the part this was tuned on; the kernel loops when there are more items than workgroups.
-void rowmean_plan(int64_t K, int64_t N, int dtype, int &strips, int &chunks, int &rows_per_chunk)
+// Column strips and row chunks of the second chain's first phase: 128-byte strips, and as many row
+// chunks as give about one (strip, chunk) item per compute unit of the part this was tuned on (the
+// kernel loops when there are more items than workgroups).  Few chunks keep the second phase's sum short.
+struct RowMeanPlan {
+    int strips, k_pad, chunks, rows_per_chunk;
+    size_t partial_bytes, cpart_bytes;
+};
+
+RowMeanPlan rowmean_plan(int64_t K, int64_t N, int dtype, int num_cus)
 {
-    const int64_t per_strip = kRowMeanColThreads * (dtype == FF_BF16 ? 8 : 4);
-    strips = (int)((K + per_strip - 1) / per_strip);
-    int64_t want = 256 / strips;
+    RowMeanPlan r{};
+    const int64_t strip_elems = 128 / (dtype == FF_BF16 ? 2 : 4);
+    r.strips = (int)((K + strip_elems - 1) / strip_elems);
+    r.k_pad = (int)(r.strips * strip_elems);
+    int64_t want = 256 / r.strips;
     if (want < 1)
         want = 1;
-    const int64_t quantum = 8 * kRowMeanColSub;  // every row group of a workgroup gets whole batches of 8 rows
-    rows_per_chunk = (int)(((N + want - 1) / want + quantum - 1) / quantum * quantum);
-    chunks = (int)((N + rows_per_chunk - 1) / rows_per_chunk);
+    const int64_t q = kRowMeanRowsPerStep;
+    r.rows_per_chunk = (int)(((N + want - 1) / want + q - 1) / q * q);
+    r.chunks = (int)((N + r.rows_per_chunk - 1) / r.rows_per_chunk);
+    r.partial_bytes = round_up((size_t)r.chunks * (size_t)r.k_pad * sizeof(float), 256);
+    r.cpart_bytes = round_up((size_t)num_cus * sizeof(float), 256);
+    return r;
 }
 
 }  // namespace
@@ -325,19 +336,18 @@ int ff_fused_linear_sub_rowmean_gelu_residual(const void *X, const void *W, cons
     if (!st)
         return FF_ERR_LAUNCH;
     RowMeanParams p{};
-    rowmean_plan(K, N, dtype, p.strips, p.chunks, p.rows_per_chunk);
-    const size_t partial_bytes = round_up((size_t)p.chunks * (size_t)K * sizeof(float), 256);
-    const size_t wbar_bytes = round_up((size_t)(K + 1) * sizeof(float), 256);
-    rc = prepare_workspace(*st, kCtrlBytes + partial_bytes + wbar_bytes, static_cast<hipStream_t>(stream));
+    const RowMeanPlan pl = rowmean_plan(K, N, dtype, st->num_cus);
+    rc = prepare_workspace(*st, kCtrlBytes + pl.partial_bytes + pl.cpart_bytes, static_cast<hipStream_t>(stream));
     if (rc != FF_OK)
         return rc;
     char *ws = static_cast<char *>(st->ws);
     p.X = X; p.W = W; p.b = b; p.s = s; p.Out = Out;
     p.partial = reinterpret_cast<float *>(ws + kCtrlBytes);
-    p.wbar = reinterpret_cast<float *>(ws + kCtrlBytes + partial_bytes);
+    p.cpart = reinterpret_cast<float *>(ws + kCtrlBytes + pl.partial_bytes);
     p.counters = reinterpret_cast<unsigned *>(ws + kCounterOffset);
     p.err = reinterpret_cast<unsigned *>(ws);
     p.M = (int)M; p.K = (int)K; p.N = (int)N;
+    p.strips = pl.strips; p.k_pad = pl.k_pad; p.chunks = pl.chunks; p.rows_per_chunk = pl.rows_per_chunk;
     p.grid = st->num_cus;  // one workgroup per compute unit, all resident: the phases meet inside the launch
     p.extra_arrivals = g_extra_arrivals;
     p.wait_ticks = g_wait_limit_us * st->ticks_per_us;
@@ -352,10 +362,9 @@ namespace {
 
 size_t rowmean_workspace_bytes(int64_t K, int64_t N, int dtype)
 {
-    int strips, chunks, rpc;
-    rowmean_plan(K, N, dtype, strips, chunks, rpc);
-    return kCtrlBytes + round_up((size_t)chunks * (size_t)K * sizeof(float), 256) +
-           round_up((size_t)(K + 1) * sizeof(float), 256);
+    // sized for any device: the per-workgroup slices take at most 1024 compute units' worth
+    const RowMeanPlan pl = rowmean_plan(K, N, dtype, 1024);
+    return kCtrlBytes + pl.partial_bytes + pl.cpart_bytes;
 }
 
 }  // namespace

@@ -11,15 +11,17 @@
 // dot product per row: O(NK + MK) work, bound by HBM traffic
 // (W + X read once, Out written once).
 //
-// One launch of one workgroup per compute unit, three phases separated by two
-// grid-wide arrivals (counters in the control region, bounded waits):
-//   1  column sums of W over chunks of rows (fp32 partials, written through);
-//      one workgroup also computes c.  Then every wavefront requests its first
-//      row of X, which travels while the grid meets.
-//   2  the first K/64 workgroups add the partials in chunk order: wbar.
-//   3  wbar moves into LDS; one wavefront per row: the row is read once and kept
-//      in registers (the case study's "cache the original row in registers"),
-//      dotted with wbar, butterfly-reduced, GELU, broadcast add, store.
+// One launch of one workgroup per compute unit, two phases separated by one
+// grid-wide arrival (counters in the control region, bounded wait):
+//   1  column sums of W: a work item is a 128-byte strip of columns times a chunk
+//      of rows, 8 lanes per row piece and 64 rows per step, reduced by shuffles and
+//      once through LDS; fp32 partials [chunks][K] are written through.  Every
+//      workgroup also sums its slice of b - s.  Then every wavefront requests its
+//      first rows of X, which travel while the grid meets.
+//   2  each workgroup adds the few chunk partials in chunk order into LDS: wbar;
+//      one wavefront per row: the row is read once and kept in registers (the
+//      case study's "cache the original row in registers"), dotted with wbar,
+//      butterfly-reduced, GELU, broadcast add, store.
 // All sums run in fixed order: results are bitwise reproducible on a device.
 #include "ff_tile.hpp"
 
@@ -27,11 +29,13 @@ namespace ff {
 
 namespace {
 
-constexpr int kColThreads = kRowMeanColThreads;  // phase 1: threads across a strip of columns, 16 bytes of a row each
-constexpr int kColSub = kRowMeanColSub;          // phase 1: groups of rows per workgroup
-constexpr int kThreads = kColThreads * kColSub;  // 512
-constexpr int kWaves = kThreads / 64;            // phase 3: rows in flight per workgroup
-constexpr int kMaxChunks = 16;                   // 16-byte chunks of a row one lane keeps in registers
+constexpr int kThreads = kRowMeanThreads;         // 512
+constexpr int kWaves = kThreads / 64;             // phase 2: rows in flight per workgroup
+constexpr int kPieces = 8;                        // 16-byte pieces of a 128-byte strip
+constexpr int kRowsPerStep = kRowMeanRowsPerStep; // phase 1: rows of W one load instruction of the workgroup covers
+constexpr int kInFlight = 8;                      // phase 1: load instructions a thread keeps in flight
+constexpr int kMaxChunks = 16;                    // 16-byte chunks of a row of X one lane keeps in registers
+static_assert(kRowsPerStep * kPieces == kThreads, "one 16-byte piece per thread per step");
 
 // a plain value another workgroup (on another XCD, behind another L2) reads later in this launch
 __device__ __forceinline__ void store_through(float *p, float v)
@@ -56,13 +60,14 @@ __device__ __forceinline__ void unpack(const uintx4 &v, float (&f)[8], const flo
         f[i] = __uint_as_float(v[i]);
 }
 
-// PL = 16-byte chunks of a row a lane keeps in registers; R = rows a wavefront requests ahead of phase 3.
+// PL = 16-byte chunks of a row a lane keeps in registers; R = rows a wavefront requests ahead of phase 2.
 template <typename T, int PL, int R>
 __global__ __launch_bounds__(kThreads) void rowmean_kernel(const RowMeanParams p)
 {
     constexpr int E = Vec16<T>::n;
-    __shared__ float red[kColSub][8 * kColThreads];  // 16 KiB; phases 2 and the c sum reuse it
-    extern __shared__ __align__(16) float s_w[];    // K floats (phase 3)
+    constexpr int kStripElems = kPieces * E;        // columns of a strip
+    __shared__ float red[kWaves][kPieces * 8];
+    extern __shared__ __align__(16) float s_w[];    // K floats (phase 2)
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = tid >> 6;
@@ -73,67 +78,83 @@ __global__ __launch_bounds__(kThreads) void rowmean_kernel(const RowMeanParams p
     T *Out = reinterpret_cast<T *>(p.Out);
 
     // ---- phase 1: partial[chunk][k] = sum over the chunk's rows of W[n][k] ----
-    // item = (column strip, row chunk); a workgroup is kColSub groups of kColThreads threads, a group
-    // adds a quarter of the chunk's rows (16 bytes of each row per thread), group 0 adds the groups
     {
-        const int col = tid % kColThreads;
-        const int sub = tid / kColThreads;
-        const int rows_per_sub = p.rows_per_chunk / kColSub;
+        const int piece = tid % kPieces;
+        const int r = tid / kPieces;
         for (int item = blockIdx.x; item < p.strips * p.chunks; item += G) {
             const int strip = item % p.strips;
             const int chunk = item / p.strips;
-            const int k0 = (strip * kColThreads + col) * E;
-            int n = chunk * p.rows_per_chunk + sub * rows_per_sub;
-            int n_end = n + rows_per_sub;
-            n_end = n_end < N ? n_end : N;
+            const int k0 = strip * kStripElems + piece * E;
+            const int n_begin = chunk * p.rows_per_chunk;
+            const int n_end = n_begin + p.rows_per_chunk < N ? n_begin + p.rows_per_chunk : N;
             float acc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
             if (k0 < K) {
-                const T *w = W + (size_t)n * K + k0;
-                for (; n + 8 <= n_end; n += 8) {  // eight rows in flight
-                    uintx4 v[8];
+                const T *w = W + k0;
+                int n = n_begin + r;
+                for (; n + (kInFlight - 1) * kRowsPerStep < n_end; n += kInFlight * kRowsPerStep) {
+                    uintx4 v[kInFlight];
 #pragma unroll
-                    for (int u = 0; u < 8; ++u)
-                        v[u] = __builtin_nontemporal_load(reinterpret_cast<const uintx4 *>(w + (size_t)u * K));
+                    for (int u = 0; u < kInFlight; ++u)
+                        v[u] = __builtin_nontemporal_load(
+                            reinterpret_cast<const uintx4 *>(w + (size_t)(n + u * kRowsPerStep) * K));
 #pragma unroll
-                    for (int u = 0; u < 8; ++u) {
+                    for (int u = 0; u < kInFlight; ++u) {
                         float f[8];
                         unpack(v[u], f, (const T *)nullptr);
 #pragma unroll
                         for (int e = 0; e < E; ++e)
                             acc[e] += f[e];
                     }
-                    w += (size_t)8 * K;
                 }
-                for (; n < n_end; ++n) {
-                    const uintx4 v = __builtin_nontemporal_load(reinterpret_cast<const uintx4 *>(w));
+                for (; n < n_end; n += kRowsPerStep) {
+                    const uintx4 v = __builtin_nontemporal_load(reinterpret_cast<const uintx4 *>(w + (size_t)n * K));
                     float f[8];
                     unpack(v, f, (const T *)nullptr);
 #pragma unroll
                     for (int e = 0; e < E; ++e)
                         acc[e] += f[e];
-                    w += K;
                 }
             }
+            // the 8 rows of a wavefront (lane / 8), fixed butterfly; lanes 0..7 end with the piece sums
+#pragma unroll
+            for (int off = 8; off <= 32; off <<= 1)
+#pragma unroll
+                for (int e = 0; e < E; ++e)
+                    acc[e] += __shfl_xor(acc[e], off);
             __syncthreads();  // the previous item's readers are done with red
+            if (lane < kPieces)
 #pragma unroll
-            for (int e = 0; e < E; ++e)
-                red[sub][col * E + e] = acc[e];
+                for (int e = 0; e < E; ++e)
+                    red[wave][lane * E + e] = acc[e];
             __syncthreads();
-            // consecutive threads write consecutive columns: whole lines go out, written through
-            for (int cidx = tid; cidx < kColThreads * E; cidx += kThreads) {
-                const int k = strip * kColThreads * E + cidx;
-                if (k < K) {
-                    float t = red[0][cidx];
+            if (tid < kStripElems) {
+                float t = red[0][tid];
 #pragma unroll
-                    for (int g = 1; g < kColSub; ++g)
-                        t += red[g][cidx];
-                    store_through(p.partial + (size_t)chunk * K + k, t);
-                }
+                for (int w8 = 1; w8 < kWaves; ++w8)
+                    t += red[w8][tid];
+                // the partial rows are padded to whole strips: columns at or beyond K hold zeros
+                store_through(p.partial + (size_t)chunk * p.k_pad + strip * kStripElems + tid, t);
             }
+        }
+        // this workgroup's slice of sum(b - s): wavefront 0, lanes stride the slice, fixed butterfly
+        if (wave == 0) {
+            const T *b = reinterpret_cast<const T *>(p.b);
+            const T *sv = reinterpret_cast<const T *>(p.s);
+            const int per = (N + G - 1) / G;
+            const int s_begin = blockIdx.x * per < N ? blockIdx.x * per : N;
+            const int s_end = s_begin + per < N ? s_begin + per : N;
+            float acc = 0.0f;
+            for (int n = s_begin + lane; n < s_end; n += 64)
+                acc += (b ? load_as_float(b + n) : 0.0f) - (sv ? load_as_float(sv + n) : 0.0f);
+#pragma unroll
+            for (int off = 32; off >= 1; off >>= 1)
+                acc += __shfl_xor(acc, off);
+            if (lane == 0)
+                store_through(p.cpart + blockIdx.x, acc);
         }
     }
 
-    // ---- arrival A: every partial is written ----
+    // ---- arrival: every partial is written ----
     wait_published();
     __syncthreads();
     const int way = blockIdx.x % kSyncWays;
@@ -169,90 +190,33 @@ __global__ __launch_bounds__(kThreads) void rowmean_kernel(const RowMeanParams p
     }
     __syncthreads();
 
-    // ---- phase 2: wbar[k] = (sum of the chunk partials in chunk order) / N ----
-    // a workgroup item owns 64 columns: 16 lanes x float4 across, 16 groups of chunks down; a thread adds
-    // its group's chunks in order, then thread k adds the 16 group sums in order
-    const int mean_items = (K + 63) / 64;
-    {
-        float(*red2)[65] = reinterpret_cast<float(*)[65]>(&red[0][0]);
-        for (int item = blockIdx.x; item < mean_items; item += G) {
-            if (tid < 256) {
-                const int col4 = tid & 15;
-                const int grp = tid >> 4;
-                const int k = item * 64 + col4 * 4;
-                const int per_grp = (p.chunks + 15) / 16;
-                const int c_begin = grp * per_grp;
-                const int c_end = (c_begin + per_grp < p.chunks) ? c_begin + per_grp : p.chunks;
-                floatx4 acc = {0.0f, 0.0f, 0.0f, 0.0f};
-                if (k < K) {
-                    const float *src = p.partial + (size_t)c_begin * K + k;
-#pragma unroll 8
-                    for (int c = c_begin; c < c_end; ++c) {
-                        acc += *reinterpret_cast<const floatx4 *>(src);
-                        src += K;
-                    }
-                }
-#pragma unroll
-                for (int e = 0; e < 4; ++e)
-                    red2[grp][col4 * 4 + e] = acc[e];
-            }
-            __syncthreads();
-            const int kk = item * 64 + tid;
-            if (tid < 64 && kk < K) {
-                float t = 0.0f;
-#pragma unroll
-                for (int g = 0; g < 16; ++g)
-                    t += red2[g][tid];
-                store_through(p.wbar + kk, t / (float)N);
-            }
-            __syncthreads();
+    // ---- phase 2: wbar into LDS (chunk partials added in chunk order), c, then one wavefront per row ----
+    // two blocks of columns per pass, so that all of a thread's loads are in flight together
+    for (int k = tid * 4; k < K; k += kThreads * 8) {
+        const int k2 = k + kThreads * 4;
+        const bool two = k2 < K;
+        const float *src0 = p.partial + k;
+        const float *src1 = p.partial + (two ? k2 : k);
+        floatx4 t0 = {0.0f, 0.0f, 0.0f, 0.0f};
+        floatx4 t1 = {0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll 4
+        for (int ch = 0; ch < p.chunks; ++ch) {
+            t0 += *reinterpret_cast<const floatx4 *>(src0);
+            t1 += *reinterpret_cast<const floatx4 *>(src1);
+            src0 += p.k_pad;
+            src1 += p.k_pad;
         }
+        *reinterpret_cast<floatx4 *>(s_w + k) = t0 / (float)N;
+        if (two)
+            *reinterpret_cast<floatx4 *>(s_w + k2) = t1 / (float)N;
     }
-
-    // ---- c = mean(b - s), by the workgroup after the last one that had phase-2 items ----
-    const int b_wgs = mean_items + 1 < G ? mean_items + 1 : G;   // workgroups that arrive at B
-    if ((int)blockIdx.x == b_wgs - 1) {
-        const T *b = reinterpret_cast<const T *>(p.b);
-        const T *sv = reinterpret_cast<const T *>(p.s);
-        float acc = 0.0f;
-        if (b)
-            for (int n = tid; n < N; n += kThreads)
-                acc += load_as_float(b + n);
-        if (sv)
-            for (int n = tid; n < N; n += kThreads)
-                acc -= load_as_float(sv + n);
-        float *flat = &red[0][0];
-        flat[tid] = acc;
-        __syncthreads();
-        for (int off = kThreads / 2; off >= 1; off >>= 1) {
-            if (tid < off)
-                flat[tid] += flat[tid + off];
-            __syncthreads();
-        }
-        if (tid == 0)
-            store_through(p.wbar + K, flat[0] / (float)N);
-    }
-
-    // ---- arrival B: wbar and c are complete (only the workgroups that wrote them arrive) ----
-    if ((int)blockIdx.x < b_wgs) {
-        wait_published();
-        __syncthreads();
-        if (tid == 0)
-            atomic_add_device(p.counters + (size_t)way * kSyncStride + 3, 1u);
-    }
-    if (wave == 0) {
-        const int l = lane < kSyncWays ? lane : 0;
-        const unsigned target = l < b_wgs ? (unsigned)(b_wgs + kSyncWays - 1 - l) / kSyncWays : 0u;
-        if (!wait_counters_wave(p.counters + 3, target + (l == 0 ? (unsigned)p.extra_arrivals : 0u), p.wait_ticks) &&
-            lane == 0)
-            atomic_store_device(p.err, 1u);
-    }
-    __syncthreads();
-
-    // ---- phase 3: Out[m] = X[m] + GELU(X[m] . wbar + c), one wavefront per row ----
-    for (int k = tid * 4; k < K; k += kThreads * 4)
-        *reinterpret_cast<floatx4 *>(s_w + k) = *reinterpret_cast<const floatx4 *>(p.wbar + k);
-    const float c = p.wbar[K];
+    float c = 0.0f;  // every wavefront adds the workgroups' slices in the same order
+    for (int j = lane; j < G; j += 64)
+        c += p.cpart[j];
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1)
+        c += __shfl_xor(c, off);
+    c /= (float)N;
     __syncthreads();
     auto finish_row = [&](int m, const uintx4 (&row)[PL]) {
         const T *x = X + (size_t)m * K;
@@ -325,7 +289,7 @@ __global__ __launch_bounds__(kThreads) void rowmean_kernel(const RowMeanParams p
     }
 
     // ---- departure: the last workgroup of the last way re-arms every counter ----
-    // (only then has every workgroup left both waits, so no poller can see a counter go back to zero)
+    // (only then has every workgroup left its wait, so no poller can see a counter go back to zero)
     if (tid == 0) {
         const unsigned in_way = (unsigned)(G + kSyncWays - 1 - way) / kSyncWays;
         const unsigned ways = G < kSyncWays ? (unsigned)G : (unsigned)kSyncWays;
@@ -334,7 +298,6 @@ __global__ __launch_bounds__(kThreads) void rowmean_kernel(const RowMeanParams p
                 for (int w = 0; w < kSyncWays; ++w) {
                     atomic_store_device(p.counters + (size_t)w * kSyncStride, 0u);
                     atomic_store_device(p.counters + (size_t)w * kSyncStride + 1, 0u);
-                    atomic_store_device(p.counters + (size_t)w * kSyncStride + 3, 0u);
                 }
                 atomic_store_device(p.counters + 2, 0u);
             }

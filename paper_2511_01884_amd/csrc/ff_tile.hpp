@@ -52,20 +52,21 @@ struct SmallMParams {
     long long wait_ticks;
 };
 
-// second chain: a workgroup is kRowMeanColSub row groups of kRowMeanColThreads column threads
-constexpr int kRowMeanColThreads = 128;
-constexpr int kRowMeanColSub = 4;
+// second chain: 512 threads; phase 1 covers 64 rows x 128 bytes of W per load instruction
+constexpr int kRowMeanThreads = 512;
+constexpr int kRowMeanRowsPerStep = 64;
 
 struct RowMeanParams {
     const void *X, *W, *b, *s;
     void *Out;
-    float *partial;      // [chunks][K] partial column sums of W
-    float *wbar;         // [K + 1]: column means of W, then c = mean(b - s)
+    float *partial;      // [chunks][k_pad] partial column sums of W
+    float *cpart;        // [grid] slices of sum(b - s)
     unsigned *counters;  // control-region counter array (zero before and after a launch)
     unsigned *err;
     int M, K, N;
-    int strips;          // column strips of kRowMeanColThreads * (16 / sizeof T) columns
-    int chunks, rows_per_chunk;  // row chunks of W; rows_per_chunk is a multiple of 8 * kRowMeanColSub
+    int strips;          // 128-byte column strips; k_pad = strips * (128 / sizeof T)
+    int k_pad;
+    int chunks, rows_per_chunk;  // row chunks of W; rows_per_chunk is a multiple of kRowMeanRowsPerStep
     int grid;            // one workgroup per compute unit: all co-resident
     int extra_arrivals;  // test hook
     long long wait_ticks;
