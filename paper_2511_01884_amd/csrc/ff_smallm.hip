@@ -284,15 +284,19 @@ __global__ __launch_bounds__(kThreads) void smallm_kernel(const SmallMParams p)
         const int s_end = (chunk + 1) * per < p.strips ? (chunk + 1) * per : p.strips;
         float na = 0.0f, mean_a = 0.0f, m2a = 0.0f;
         for (int s0 = s_begin; s0 < s_end; s0 += 8) {
-            floatx2 u[8];  // issue the loads together, then merge in order
+            floatx2 u[8];  // eight loads issued together (never branching: past the end the last
+                           // strip is read again and enters the merge with zero columns), merged in order
 #pragma unroll
-            for (int j = 0; j < 8; ++j)
-                if (s0 + j < s_end)
-                    u[j] = p.partials[(size_t)(s0 + j) * kRows + row];
+            for (int j = 0; j < 8; ++j) {
+                const int sj = s0 + j < s_end ? s0 + j : s_end - 1;
+                u[j] = p.partials[(size_t)sj * kRows + row];
+            }
 #pragma unroll
-            for (int j = 0; j < 8; ++j)
-                if (s0 + j < s_end)
-                    merge_stats(na, mean_a, m2a, cols_of(s0 + j, s0 + j + 1), u[j][0], u[j][1]);
+            for (int j = 0; j < 8; ++j) {
+                const bool live = s0 + j < s_end;
+                merge_stats(na, mean_a, m2a, live ? cols_of(s0 + j, s0 + j + 1) : 0.0f, u[j][0],
+                            live ? u[j][1] : 0.0f);
+            }
         }
         // fold the wave's chunks: lane takes the later chunk from lane + kRows * step
 #pragma unroll
