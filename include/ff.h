@@ -212,9 +212,9 @@ int ff_debug_force_variant(int variant);
  * counters when the traffic of the other kernels is measured. */
 int ff_debug_copy(const void *src, void *dst, size_t bytes, void *stream);
 
-/* Tile shape of the tiled variants for later calls: tile = 0 (automatic), 128 or 256;
- * wg_per_cu = 0 or 1 (a persistent grid of one workgroup per compute unit) or 2 (two, with
- * 128-tiles only).  The automatic choice is the fastest on every measured shape; the other
+/* Tile shape of the tiled variants for later calls: tile = 0 (automatic), 64, 128 or 256;
+ * wg_per_cu = 0 (automatic), 1 (a persistent grid of one workgroup per compute unit) or 2 (two,
+ * not with 256-tiles).  The automatic choice is the fastest on every measured shape; the other
  * shapes exist as distinct kernels of the same operator for the profiling-metric study and
  * for tests.  FF_ERR_UNSUPPORTED for any other combination. */
 int ff_debug_force_tile(int tile, int wg_per_cu);

@@ -29,7 +29,7 @@ DeviceState g_dev[kMaxDevices];
 int g_forced_variant = FF_VARIANT_AUTO;
 long long g_wait_limit_us = 2000000;
 int g_extra_arrivals = 0;
-int g_forced_tile = 0;        // 0 = automatic, else 128 or 256
+int g_forced_tile = 0;        // 0 = automatic, else 64, 128 or 256
 int g_forced_wg_per_cu = 0;   // 0 = automatic (one workgroup per compute unit), else 1 or 2
 thread_local int t_last_variant = 0;
 
@@ -91,9 +91,11 @@ int make_plan(int64_t M, int64_t K, int64_t N, int dtype, int num_cus, int force
     }
 
     // tiled variants: 256x256 tiles unless they would fill at most half of the compute units (then the
-    // 128-tiles, two per compute unit, finish in one round and are faster; measured)
+    // 128-tiles, two per compute unit, finish in one round and are faster; measured); problems of at
+    // most a quarter of the compute units' worth of 128-tiles take 64-tiles, which spread them further
     const int64_t tiles256 = ((M + 255) / 256) * ((N + 255) / 256);
-    pl.tile = tiles256 * 2 > num_cus ? 256 : 128;
+    const int64_t tiles128 = ((M + 127) / 128) * ((N + 127) / 128);
+    pl.tile = tiles256 * 2 > num_cus ? 256 : (tiles128 * 4 > num_cus ? 128 : 64);
     if (g_forced_tile != 0)
         pl.tile = g_forced_tile;
     const int64_t RB = (M + pl.tile - 1) / pl.tile;
@@ -105,7 +107,7 @@ int make_plan(int64_t M, int64_t K, int64_t N, int dtype, int num_cus, int force
     const int64_t total = RB * NT;
     // two 128-tiles fit a compute unit's LDS and registers at once (measured faster than one on every
     // shape); a 256-tile takes all of both
-    const int64_t grid_cap = (int64_t)num_cus * ((pl.tile == 128 && g_forced_wg_per_cu != 1) ? 2 : 1);
+    const int64_t grid_cap = (int64_t)num_cus * ((pl.tile != 256 && g_forced_wg_per_cu != 1) ? 2 : 1);
     pl.grid = (int)(total < grid_cap ? total : grid_cap);
     pl.rounds = (int)((total + pl.grid - 1) / pl.grid);
     const bool fused_ok = NT <= pl.grid;
@@ -595,8 +597,8 @@ int ff_debug_force_variant(int variant)
 
 int ff_debug_force_tile(int tile, int wg_per_cu)
 {
-    if ((tile != 0 && tile != 128 && tile != 256) || wg_per_cu < 0 || wg_per_cu > 2 ||
-        (wg_per_cu == 2 && tile != 128))
+    if ((tile != 0 && tile != 64 && tile != 128 && tile != 256) || wg_per_cu < 0 || wg_per_cu > 2 ||
+        (wg_per_cu == 2 && tile != 128 && tile != 64))
         return FF_ERR_UNSUPPORTED;
     std::lock_guard<std::mutex> lock(g_mutex);
     g_forced_tile = tile;

@@ -277,23 +277,23 @@ __global__ __launch_bounds__(kThreads) void tile_kernel(const TileParams p)
             for (int x = 0; x < WTN + WTM; ++x)
                 read_one(slab, s, x, a, b);
         };
-        // the MFMAs are issued in kGroups groups of kPerGroup fragment pairs
+        // the MFMAs of a k-step are issued in kGroups groups (one per fragment read); group g takes the
+        // fragment pairs [g * kPairs / kGroups, (g + 1) * kPairs / kGroups): two each for 4 x 4 blocks per
+        // wave, one each for 2 x 2, and for a single block the second group takes the only pair
         constexpr int kGroups = WTN + WTM;
-        constexpr int kPerGroup = WTN * WTM / kGroups;
-        static_assert(kPerGroup * kGroups == WTN * WTM, "pairs must split evenly over the groups");
-        static_assert(kPerGroup == 1 || kPerGroup == 2, "pin_order takes one or two accumulators");
+        constexpr int kPairs = WTN * WTM;
+        static_assert(kPairs <= 2 * kGroups, "pin_order takes at most two accumulators");
         auto mma_group = [&](int g, const uintx4 (&a)[WTN], const uintx4 (&b)[WTM]) {
 #pragma unroll
-            for (int q = 0; q < kPerGroup; ++q) {
-                const int pair = g * kPerGroup + q;
+            for (int pair = g * kPairs / kGroups; pair < (g + 1) * kPairs / kGroups; ++pair)
                 Mma<T>::step(a[pair / WTM], b[pair % WTM], acc[pair / WTM][pair % WTM]);
-            }
         };
         auto pin_group = [&](int g) {
-            const int p0 = g * kPerGroup;
-            if (kPerGroup == 2)
+            const int p0 = g * kPairs / kGroups;
+            const int n = (g + 1) * kPairs / kGroups - p0;
+            if (n == 2)
                 pin_order(acc[p0 / WTM][p0 % WTM], acc[(p0 + 1) / WTM][(p0 + 1) % WTM]);
-            else
+            else if (n == 1)
                 pin_order(acc[p0 / WTM][p0 % WTM]);
         };
         auto mma_all = [&](const uintx4 (&a)[WTN], const uintx4 (&b)[WTM]) {
@@ -716,10 +716,12 @@ hipError_t launch_tile_kernel(bool bf16, int tile, int mode, const TileParams &p
     }
     if (bf16) {
         if (tile == 256) { FF_DISPATCH(__bf16, 4) }
-        FF_DISPATCH(__bf16, 2)
+        if (tile == 128) { FF_DISPATCH(__bf16, 2) }
+        FF_DISPATCH(__bf16, 1)
     }
     if (tile == 256) { FF_DISPATCH(float, 4) }
-    FF_DISPATCH(float, 2)
+    if (tile == 128) { FF_DISPATCH(float, 2) }
+    FF_DISPATCH(float, 1)
 #undef FF_DISPATCH
 }
 

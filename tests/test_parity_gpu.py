@@ -49,7 +49,7 @@ def test_full_matrix_parity(M, K, N, dtype, variant, expect):
     print(stats)
 
 
-@pytest.mark.parametrize("tile,per_cu", [(128, 1), (128, 2), (256, 1)])
+@pytest.mark.parametrize("tile,per_cu", [(64, 1), (64, 2), (128, 1), (128, 2), (256, 1)])
 @pytest.mark.parametrize("variant", [FUSED, TWOPASS])
 def test_forced_tile_shapes_parity(tile, per_cu, variant):
     """The tile shapes the automatic plan does not pick for this size are kernels of the same
@@ -66,7 +66,24 @@ def test_forced_tile_shapes_parity(tile, per_cu, variant):
     with pytest.raises(B.FFError):
         B.ff_debug_force_tile(256, 2)
     with pytest.raises(B.FFError):
-        B.ff_debug_force_tile(64, 1)
+        B.ff_debug_force_tile(32, 1)
+
+
+@pytest.mark.parametrize("M,K,N,dtype", [(256, 512, 512, "f32"), (77, 36, 132, "f32"), (129, 64, 8, "bf16"),
+                                         (1, 8, 8, "bf16"), (200, 1000, 72, "bf16")])
+def test_64_tiles_small_shapes(M, K, N, dtype):
+    """The smallest tile shape on small and ragged problems, fused and two-pass."""
+    _announce("tile 64", M, K, N, dtype)
+    d = make_inputs(M, K, N, dtype, seed=15)
+    ref = oracle_on(d)
+    for variant in (FUSED, TWOPASS):
+        B.ff_debug_force_tile(64, 0)
+        try:
+            Y, used = gpu_run(d, variant)
+        finally:
+            B.ff_debug_force_tile(0, 0)
+        assert used == variant
+        print(check_against_oracle(Y, ref, dtype, "tile 64 %dx%dx%d" % (M, K, N)))
 
 
 SMALLM_CASES = [(16, 8192, 8192), (16, 1024, 1024), (5, 520, 1000), (32, 1024, 2048),
