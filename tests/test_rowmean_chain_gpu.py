@@ -61,3 +61,56 @@ def test_rowmean_chain_optional_vectors_and_errors():
                                                     torch.zeros(8, 12, device="cuda", dtype=torch.bfloat16),
                                                     None, None)
     assert e.value.status == 5
+
+
+def test_rowmean_chain_expired_wait_is_reported_not_hung():
+    """Forced from the host: the grid-wide arrival waits for one workgroup more than exists, with a
+    3 ms limit.  The kernel must finish, flag the device error once, and the next call must be right."""
+    X, W, b, s = _inputs(700, 520, 264, "bf16", seed=33)
+    B.ff_debug_set_wait_limit_us(3000)
+    B.ff_debug_expect_extra_arrivals(1)
+    try:
+        B.ff_fused_linear_sub_rowmean_gelu_residual(X.cuda(), W.cuda(), b.cuda(), s.cuda())
+        with pytest.raises(B.FFError) as e:
+            B.ff_check_device()
+        assert e.value.status == 8
+    finally:
+        B.ff_debug_expect_extra_arrivals(0)
+        B.ff_debug_set_wait_limit_us(2000000)
+    B.ff_check_device()
+    Out = B.ff_fused_linear_sub_rowmean_gelu_residual(X.cuda(), W.cuda(), b.cuda(), s.cuda())
+    B.ff_check_device()
+    ref = oracle.linear_sub_rowmean_gelu_residual(to_np32(X), to_np32(W), to_np32(b), to_np32(s))
+    check_against_oracle(Out, ref, "bf16")
+
+
+def test_rowmean_chain_graph_replay_matches_eager():
+    """Capturable (no allocation or memset once the workspace exists; the counters re-arm themselves):
+    every replay, with fresh inputs and eager work in between, equals the eager result bit for bit."""
+    M, K, N = 2500, 1032, 776
+    X, W, b, s = _inputs(M, K, N, "bf16", seed=34)
+    Xd, Wd, bd, sd = X.cuda(), W.cuda(), b.cuda(), s.cuda()
+    out_static = torch.empty_like(Xd)
+    B.ff_fused_linear_sub_rowmean_gelu_residual(Xd, Wd, bd, sd, Out=out_static)   # warm-up: workspace exists
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    st = torch.cuda.Stream()
+    with torch.cuda.stream(st):
+        with torch.cuda.graph(g, stream=st):
+            B.ff_fused_linear_sub_rowmean_gelu_residual(Xd, Wd, bd, sd, Out=out_static)
+    torch.cuda.synchronize()
+    for rep in range(4):
+        X2, W2, _, _ = _inputs(M, K, N, "bf16", seed=200 + rep)
+        Xd.copy_(X2.cuda())
+        Wd.copy_(W2.cuda())
+        torch.cuda.synchronize()
+        eager = B.ff_fused_linear_sub_rowmean_gelu_residual(Xd, Wd, bd, sd).clone()
+        torch.cuda.synchronize()
+        out_static.zero_()
+        g.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(out_static, eager), "replay %d differs from eager" % rep
+    B.ff_check_device()
+    ref = oracle.linear_sub_rowmean_gelu_residual(to_np32(Xd.cpu()), to_np32(Wd.cpu()), to_np32(b), to_np32(s),
+                                                  rows=list(range(0, M, 97)))
+    check_against_oracle(out_static[torch.arange(0, M, 97)], ref, "bf16")

@@ -116,3 +116,48 @@ def test_xent_argument_errors():
     assert lib.ff_cross_entropy_mean(None, None, 0, 8, 0, None, None, None) == 2      # FF_ERR_SHAPE
     assert lib.ff_cross_entropy_mean(None, None, 4, 8, 7, None, None, None) == 3      # FF_ERR_DTYPE
     assert B.ff_cross_entropy_workspace_bytes(4, 8, 0) > 0 and B.ff_cross_entropy_workspace_bytes(0, 8, 0) == 0
+
+
+def test_xent_graph_replay_matches_eager():
+    """Capturable (no allocation or memset once the workspace exists; the arrival counter is back at zero
+    after every launch): every replay, with fresh logits and eager work in between, equals the eager result."""
+    Bn, C = 6000, 1500
+    logits, targets = make_xent_inputs(Bn, C, "f32", seed=8)
+    Ld, td = logits.cuda(), targets.cuda()
+    mean_s = torch.empty(1, device="cuda")
+    rows_s = torch.empty(Bn, device="cuda")
+    B.ff_cross_entropy_mean(Ld, td, row_loss=rows_s, mean_loss=mean_s)   # warm-up: workspace exists
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    st = torch.cuda.Stream()
+    with torch.cuda.stream(st):
+        with torch.cuda.graph(g, stream=st):
+            B.ff_cross_entropy_mean(Ld, td, row_loss=rows_s, mean_loss=mean_s)
+    torch.cuda.synchronize()
+    for rep in range(4):
+        l2, t2 = make_xent_inputs(Bn, C, "f32", seed=300 + rep)
+        Ld.copy_(l2.cuda())
+        td.copy_(t2.cuda())
+        torch.cuda.synchronize()
+        m_e, r_e = B.ff_cross_entropy_mean(Ld, td, with_rows=True)
+        torch.cuda.synchronize()
+        mean_s.zero_()
+        rows_s.zero_()
+        g.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(mean_s, m_e) and torch.equal(rows_s, r_e), "replay %d differs from eager" % rep
+    ref_rows, ref_mean = oracle.cross_entropy(Ld.cpu().numpy(), td.cpu().numpy())
+    assert np.abs(rows_s.cpu().double().numpy() - ref_rows).max() <= GATE
+    assert abs(float(mean_s.cpu()[0]) - ref_mean) <= GATE
+
+
+def test_xent_full_size_bf16_sampled_against_oracle():
+    """bf16 logits at a large size: rows checked one by one on a sample, the mean through the library's rows."""
+    Bn, C = 16384, 8192
+    logits, targets = make_xent_inputs(Bn, C, "bf16", seed=9, scale=3.0)
+    mean, rows = B.ff_cross_entropy_mean(logits.cuda(), targets.cuda(), with_rows=True)
+    torch.cuda.synchronize()
+    idx = np.unique(np.concatenate([[0, 1, Bn - 1], np.random.default_rng(0).integers(0, Bn, 200)]))
+    ref_rows, _ = oracle.cross_entropy(logits[idx].float().numpy(), targets[idx].numpy())
+    assert np.abs(rows.cpu().double().numpy()[idx] - ref_rows).max() <= GATE
+    assert abs(float(mean.cpu()[0]) - rows.cpu().double().numpy().mean()) <= 1e-5
