@@ -86,7 +86,7 @@ def main() -> int:
 
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU; the path shards by rows with no exchange "
-              "(see DESIGN.md), and no multi-GPU figure is produced. Re-run with --gpus 1.",
+              "(rows are independent: replicate W, split M), and no multi-GPU figure is produced. Re-run with --gpus 1.",
               file=sys.stderr)
         return 2
 
