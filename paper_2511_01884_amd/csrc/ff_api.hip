@@ -448,8 +448,12 @@ int ff_metric_select_host(const double *r, const uint8_t *keep, int64_t n_tasks,
     if (n_tasks <= 0 || n_metrics <= 0 || top_k <= 0 || n_tasks > 1 << 20 || n_metrics > 1 << 24 ||
         !(percentile >= 0.0 && percentile <= 100.0) || min_tasks < 1)
         return FF_ERR_SHAPE;
-    metric_select_host(r, keep, (int)n_tasks, (int)n_metrics, top_k, percentile, min_tasks, top, score,
-                       selected, threshold);
+    try {
+        metric_select_host(r, keep, (int)n_tasks, (int)n_metrics, top_k, percentile, min_tasks, top, score,
+                           selected, threshold);
+    } catch (...) {  // host allocation failed: nothing may leave through the C boundary
+        return FF_ERR_WORKSPACE;
+    }
     return FF_OK;
 }
 
@@ -471,6 +475,7 @@ int ff_metric_selection(const double *values, const double *runtime, int64_t n_t
         return FF_ERR_ALIGN;
     const int n = (int)n_tasks, V = (int)n_kernels, J = (int)n_metrics;
     hipStream_t st_stream = static_cast<hipStream_t>(stream);
+    try {
     std::vector<double> r((size_t)n * J);
     std::vector<uint8_t> keep;
     {
@@ -513,6 +518,9 @@ int ff_metric_selection(const double *values, const double *runtime, int64_t n_t
                        score_host, selected_host, threshold_host);
     if (r_host)
         std::copy(r.begin(), r.end(), r_host);
+    } catch (...) {  // host allocation failed: nothing may leave through the C boundary
+        return FF_ERR_WORKSPACE;
+    }
     return FF_OK;
 }
 
