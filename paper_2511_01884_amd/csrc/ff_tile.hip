@@ -150,6 +150,7 @@ __global__ __launch_bounds__(kThreads) void tile_kernel(const TileParams p)
     const int dma_r = lane / kChunksPerRow;
     const int dma_cs = lane % kChunksPerRow;
 
+    bool first_tile = true;
     for (int t = blockIdx.x; t < p.rounds * (int)gridDim.x; t += gridDim.x) {
         // ---- tile coordinates (XCD-aware order inside a round when enabled) ----
         int rb, cb;
@@ -322,15 +323,20 @@ __global__ __launch_bounds__(kThreads) void tile_kernel(const TileParams p)
                 issue_cut(slab, half);
             }
         };
-        __syncthreads();  // previous tile's epilogue is done with the LDS
+        // The previous tile's epilogue is done with the LDS once every wave is here (its LDS reads
+        // completed before its stores could issue).  No wait for those stores: they drain while the
+        // first slab of this tile travels.
+        lds_barrier();
         dma_half_any(0, 0);
         dma_half_any(0, 1);
         if (slabs > 1)
             dma_half_any(1, 0);
-        if (slabs > 1 && !(k_ragged && slabs == 2))
+        if (first_tile && slabs > 1 && !(k_ragged && slabs == 2))
             __builtin_amdgcn_s_waitcnt(0x0f70 | (kDmaA & 15) | ((kDmaA >> 4) << 14));  // slab 0 landed
         else
-            __builtin_amdgcn_s_waitcnt(0x0f70);  // vmcnt(0)
+            __builtin_amdgcn_s_waitcnt(0x0f70);  // vmcnt(0): also the previous tile's stores, whose
+                                                 // completion order relative to loads is not relied on
+        first_tile = false;
         lds_barrier();
         load_frags(0, 0, fa[0], fb[0]);
 
@@ -568,14 +574,6 @@ __global__ __launch_bounds__(kThreads) void tile_kernel(const TileParams p)
                 s_rst[tid] = o;
             }
             __syncthreads();
-            if (tid == 0) {
-                // the last tile to have read the partials re-arms the counters
-                unsigned *cnt = p.counters + 2 * (size_t)rb;
-                if (atomic_add_device(cnt + 1, 1u) == (unsigned)p.NT - 1u) {
-                    atomic_store_device(cnt, 0u);
-                    atomic_store_device(cnt + 1, 0u);
-                }
-            }
         }
 
         // ---- (normalise,) convert, transpose through LDS, store 16-byte rows ----
@@ -631,6 +629,16 @@ __global__ __launch_bounds__(kThreads) void tile_kernel(const TileParams p)
                     *reinterpret_cast<uintx4 *>(out_base + (size_t)gm * N + gn) = v;
             }
             wave_lds_sync();
+        }
+        if (MODE == kFused && tid == 0) {
+            // Departure, after the stores have been issued so that the wait for the counter's old value
+            // delays nothing: the last tile of the row-block to get here re-arms its counters (every
+            // tile of the row-block has read the partials by then).
+            unsigned *cnt = p.counters + 2 * (size_t)rb;
+            if (atomic_add_device(cnt + 1, 1u) == (unsigned)p.NT - 1u) {
+                atomic_store_device(cnt, 0u);
+                atomic_store_device(cnt + 1, 0u);
+            }
         }
         }  // epilogue scope
     }
