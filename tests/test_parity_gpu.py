@@ -146,6 +146,21 @@ def test_benchmark_sizes_sampled_rows(name):
     assert float((T.var(dim=1, unbiased=False) - 1).abs().max()) < 2e-2
 
 
+@pytest.mark.parametrize("name", ["cfg1", "cfg2"])
+def test_benchmark_sizes_full_matrix(name):
+    """Every element of the two benchmark shapes the oracle finishes in seconds on the host's threads,
+    in the launch configuration the benchmark times; a second run must give the same bits."""
+    wl = CONFIGS[name]
+    _announce("full matrix", name)
+    d = make_inputs(wl.M, wl.K, wl.N, wl.dtype, seed=0)
+    Y, used = gpu_run(d, AUTO)
+    assert used == FUSED
+    stats = check_against_oracle(Y, oracle_on(d), wl.dtype, name + " full")
+    print(name, stats)
+    Y2, _ = gpu_run(d, AUTO)
+    assert torch.equal(Y, Y2)
+
+
 def test_wide_rows_plain_affine_moments():
     """gamma = 1, beta = 0 on the wide-row workload: every output row has mean 0 and
     biased variance var/(var+eps) ~ 1, up to bf16 output rounding."""
