@@ -146,6 +146,20 @@ def test_benchmark_sizes_sampled_rows(name):
     assert float((T.var(dim=1, unbiased=False) - 1).abs().max()) < 2e-2
 
 
+def test_rows_wider_than_the_grid_take_the_two_pass_path_by_themselves():
+    """N = 258 tiles of 256 columns: more tiles per row than co-resident workgroups, so the automatic
+    plan must pick the two-pass variant (and a forced single-pass must refuse); maximum-width coverage."""
+    M, K, N = 40, 64, 258 * 256
+    _announce("wide", M, K, N)
+    d = make_inputs(M, K, N, "bf16", seed=17)
+    Y, used = gpu_run(d, AUTO)
+    assert used == TWOPASS
+    print(check_against_oracle(Y, oracle_on(d), "bf16", "40x64x66048"))
+    with pytest.raises(B.FFError) as e:
+        gpu_run(d, FUSED)
+    assert e.value.status == 5
+
+
 @pytest.mark.parametrize("name", ["cfg1", "cfg2"])
 def test_benchmark_sizes_full_matrix(name):
     """Every element of the two benchmark shapes the oracle finishes in seconds on the host's threads,
