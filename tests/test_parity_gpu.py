@@ -342,3 +342,40 @@ def test_workspace_grows_between_shapes():
         d = make_inputs(M, K, N, "bf16", seed=23)
         Y, _ = gpu_run(d, TWOPASS)
         check_against_oracle(Y, oracle_on(d), "bf16")
+
+
+# ------------------------------------------------------------ more edge cases
+def test_many_rounds_and_a_row_tail():
+    """A tall problem: 1172 row-blocks over a grid of one workgroup per compute unit (five rounds), the
+    last row-block with 61 rows; checked on sampled complete rows including the last ones."""
+    M, K, N = 300_093, 64, 256
+    _announce("tall", M, K, N)
+    d = make_inputs(M, K, N, "bf16", seed=18)
+    Y, used = gpu_run(d, AUTO)
+    assert used == FUSED
+    rows = sorted(set(sample_rows(M, 40) + [M - 1, M - 61, M - 62, 255, 256]))
+    print(check_against_oracle(Y[torch.tensor(rows)], oracle_on(d, rows=rows), "bf16", "tall"))
+
+
+@pytest.mark.parametrize("M,K,N", [(300, 128, 520), (16, 512, 1024)])
+def test_nan_and_inf_stay_in_their_rows(M, K, N):
+    """No checking on the device: a NaN or an infinity in a row of X poisons that row of Y and nothing
+    else (rows are independent; the statistics of the other rows never see it)."""
+    d = make_inputs(M, K, N, "bf16", seed=19)
+    ref = oracle_on(d)
+    X = d["X"].clone()
+    X[3, 5] = float("nan")
+    X[7, 0] = float("inf")
+    Y, _ = gpu_run(dict(d, X=X), AUTO)
+    Yc = Y.float().cpu()
+    assert bool(torch.isnan(Yc[3]).all()) and bool(torch.isnan(Yc[7]).all())
+    ok = [m for m in range(M) if m not in (3, 7)]
+    check_against_oracle(Y[torch.tensor(ok)], ref[ok], "bf16")
+
+
+@pytest.mark.parametrize("eps", [0.0, 1e-12, 0.25])
+def test_eps_values(eps):
+    d = make_inputs(130, 96, 264, "f32", seed=20)
+    d = dict(d, eps=eps)
+    Y, _ = gpu_run(d, AUTO)
+    print(check_against_oracle(Y, oracle_on(d), "f32", "eps %g" % eps))
