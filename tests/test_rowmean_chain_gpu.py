@@ -22,7 +22,9 @@ def _inputs(M, K, N, dtype, seed):
 
 
 CASES = [(37, 72, 40, "bf16"), (300, 200, 520, "f32"), (5, 8, 8, "bf16"), (1, 8, 8, "f32"),
-         (1030, 1024, 2048, "bf16"), (9, 16896, 24, "bf16"), (6, 8448, 16, "f32")]
+         (1030, 1024, 2048, "bf16"), (9, 16896, 24, "bf16"), (6, 8448, 16, "f32"),
+         (3, 32768, 40, "bf16"), (2, 32768, 8, "f32"),     # the longest supported rows (128 KiB of LDS)
+         (5000, 72, 1000, "bf16")]                         # several rows per wavefront, short rows
 
 
 @pytest.mark.parametrize("M,K,N,dtype", CASES)
@@ -60,6 +62,14 @@ def test_rowmean_chain_optional_vectors_and_errors():
         B.ff_fused_linear_sub_rowmean_gelu_residual(torch.zeros(4, 12, device="cuda", dtype=torch.bfloat16),
                                                     torch.zeros(8, 12, device="cuda", dtype=torch.bfloat16),
                                                     None, None)
+    assert e.value.status == 5
+
+
+def test_rowmean_chain_rows_too_long_are_refused():
+    X = torch.zeros(2, 32776, device="cuda", dtype=torch.bfloat16)
+    W = torch.zeros(8, 32776, device="cuda", dtype=torch.bfloat16)
+    with pytest.raises(B.FFError) as e:
+        B.ff_fused_linear_sub_rowmean_gelu_residual(X, W, None, None)
     assert e.value.status == 5
 
 
