@@ -29,17 +29,18 @@ INFINITY_CACHE_BYTES = 256 << 20
 # HBM traffic per launch of the dominant kernel, from two `rocprofv3 --pmc` runs (FETCH_SIZE, then
 # WRITE_SIZE, KiB per dispatch), each scaled by what the same counter reads for the library's plain
 # copy kernel on 256 MiB (`--workload copy`): FETCH_SIZE reads 131080 for 262144 KiB -> factor 2.0;
-# WRITE_SIZE 262140 -> 1.0.  An entry is valid only for the device sources of its kernel as they were
-# when the counters were taken: `traffic` is null once their hash differs.
-COMMON_SOURCES = ["ff_device.hpp", "ff_tile.hpp"]
+# WRITE_SIZE 262140 -> 1.0.  An entry is valid only for the device sources of its kernel (its .hip file
+# and the shared device helpers) as they were when the counters were taken: `traffic` is null once
+# their hash differs.
+COMMON_SOURCES = ["ff_device.hpp"]   # device helpers every kernel includes
 TRAFFIC = {
-    "cfg1": {"sources": ["ff_tile.hip"], "sha256": "01ea34ea144cba39b8dda4a44a716a4e6e33c21a649d51d4b37159d56aa188ce",
+    "cfg1": {"sources": ["ff_tile.hip"], "sha256": "81be6abdc42f2fe6e498bfcae267c6fd21de67d52cfe9b302f679dbfb1b1b75a",
              "bytes": int((102904.8 * 2.0 + 44305.0 * 1.0) * 1024)},
-    "cfg3": {"sources": ["ff_smallm.hip"], "sha256": "16417aaff480d0a2a84c5ccdf5516bed4b093ff16df54714c804543a04d0eb47",
+    "cfg3": {"sources": ["ff_smallm.hip"], "sha256": "b75c3641423a14dfe8a79ac4c1c098623b2ddd777cd203e3adccd5ce1b50cc63",
              "bytes": int((66907.5 * 2.0 + 339.0 * 1.0) * 1024)},
-    "xent": {"sources": ["ff_xent.hip"], "sha256": "b914051ae45f8052d7d070158e7b3b75bf58f499ddda4442bc42d53f988f2aa7",
+    "xent": {"sources": ["ff_xent.hip"], "sha256": "8fd3aee1b79a73ac01e468b0be6fa332a2711ac42a9f1ba4e514bff7949f8962",
              "bytes": int((262698.8 * 2.0 + 128.1 * 1.0) * 1024)},
-    "rowmean": {"sources": ["ff_rowmean.hip"], "sha256": "ad50f65ca61dc3b14daf3ce88a349bea9878447d5025a122a90673fd3349fc90",
+    "rowmean": {"sources": ["ff_rowmean.hip"], "sha256": "67fcc8c8610f6ba097e60712b1e48f9e71047361a63e66027e978c7a54614d0c",
              "bytes": int((33202.0 * 2.0 + 32880.7 * 1.0) * 1024)},
 }
 
@@ -60,6 +61,48 @@ def measured_traffic(workload: str):
     return t["bytes"]
 
 
+def sustained_ceiling(torch, B, bound: str):
+    """What the chip sustains at all, from the library's two do-nothing-else kernels: an MFMA-only loop
+    (bf16) or a streaming read of 1 GiB.  Reported beside the published peak, never instead of it."""
+    ev0 = torch.cuda.Event(enable_timing=True)
+    ev1 = torch.cuda.Event(enable_timing=True)
+    if bound == "mfma":
+        B.ff_debug_mfma_loop(2000)
+        torch.cuda.synchronize()
+        ev0.record()
+        flops = B.ff_debug_mfma_loop(40000)          # about 10 ms
+        ev1.record()
+        torch.cuda.synchronize()
+        return {"value": flops / (ev0.elapsed_time(ev1) * 1e-3) / 1e12, "unit": "TFLOP/s",
+                "what": "register-resident loop of bf16 32x32x16 MFMAs, four wavefronts per compute unit"}
+    buf = torch.empty(1 << 30, dtype=torch.uint8, device="cuda").random_(0, 255)
+    B.ff_debug_stream_read(buf)
+    torch.cuda.synchronize()
+    ev0.record()
+    n = 0
+    for _ in range(10):
+        n += B.ff_debug_stream_read(buf)
+    ev1.record()
+    torch.cuda.synchronize()
+    return {"value": n / (ev0.elapsed_time(ev1) * 1e-3) / 1e9, "unit": "GB/s",
+            "what": "streaming read of 1 GiB, 16-byte loads, eight in flight per thread"}
+
+
+def batch_median_ms(torch, step, launches: int = 100, batches: int = 5) -> float:
+    """Median over batches of the mean launch time between two events (the protocol's second figure)."""
+    out = []
+    for _ in range(batches):
+        e0 = torch.cuda.Event(enable_timing=True)
+        e1 = torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for i in range(launches):
+            step(i)
+        e1.record()
+        torch.cuda.synchronize()
+        out.append(e0.elapsed_time(e1) / launches)
+    return sorted(out)[len(out) // 2]
+
+
 def algorithmic_bytes(M, K, N, esize):
     """Each of X, W, b, gamma, beta read once and Y written once."""
     return (M * K + N * K + M * N + 3 * N) * esize
@@ -71,12 +114,14 @@ def main() -> int:
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="cfg1",
-                    help="cfg0..cfg4 (default: cfg1, the metric's workload), or rowmean "
+                    help="cfg0..cfg4 (default: cfg1, the metric's workload), f32_4096, copy (counter calibration), rowmean "
                          "(second fused chain: Linear, subtract, row-mean, GELU, residual add; bf16 4096^3), or xent "
                          "(row-wise cross-entropy with mean, fp32 32768 x 4096)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-eager", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="target CPU time of the oracle sample")
+    ap.add_argument("--no-extras", action="store_true",
+                    help="skip the batch-median, cache-warm and sustained-ceiling figures")
     ap.add_argument("--print-source-hash", action="store_true", help="print the kernel source hash and exit")
     args = ap.parse_args()
     if args.print_source_hash:
@@ -161,6 +206,13 @@ def main() -> int:
     roof["frac"] = roof["achieved"] / roof["peak"]
     roof["traffic"] = measured_traffic(args.workload)
     roof["kernel_ms"] = ms_kernel
+    if not args.no_extras:
+        launches = 100 if ms_kernel < 0.5 else 20
+        roof["batch_median_ms"] = batch_median_ms(torch, step, launches)
+        roof["cache_warm_ms"] = batch_median_ms(torch, lambda i: step(0), launches, 3)   # one buffer set only
+        if wl.dtype == "bf16" or hbm_bound:
+            roof["sustained"] = sustained_ceiling(torch, B, roof["bound"])
+            roof["frac_of_sustained"] = roof["achieved"] / roof["sustained"]["value"]
 
     out = {
         "metric": "TFLOP/s and % of bf16 MFMA peak (GB/s for small-M) for fused linear+GELU+LN",
@@ -265,6 +317,10 @@ def bench_rowmean(args, torch, B) -> int:
                      "unit": "GB/s", "frac": abytes / (ms_kernel * 1e-3) / 1e9 / PEAK_HBM_GBS,
                      "traffic": measured_traffic("rowmean"), "kernel_ms": ms_kernel},
     }
+    if not args.no_extras:
+        out["roofline"]["batch_median_ms"] = batch_median_ms(torch, step)
+        out["roofline"]["sustained"] = sustained_ceiling(torch, B, "hbm")
+        out["roofline"]["frac_of_sustained"] = out["roofline"]["achieved"] / out["roofline"]["sustained"]["value"]
     if not args.no_eager:
         def eager(i):
             X, W, _ = sets[i % n_sets]
@@ -363,6 +419,10 @@ def bench_xent(args, torch, B) -> int:
                      "unit": "GB/s", "frac": abytes / (ms_kernel * 1e-3) / 1e9 / PEAK_HBM_GBS,
                      "traffic": measured_traffic("xent"), "kernel_ms": ms_kernel},
     }
+    if not args.no_extras:
+        out["roofline"]["batch_median_ms"] = batch_median_ms(torch, step)
+        out["roofline"]["sustained"] = sustained_ceiling(torch, B, "hbm")
+        out["roofline"]["frac_of_sustained"] = out["roofline"]["achieved"] / out["roofline"]["sustained"]["value"]
     if not args.no_eager:
         def eager(i):
             L, t, _ = sets[i % n_sets]

@@ -212,6 +212,14 @@ int ff_debug_force_variant(int variant);
  * counters when the traffic of the other kernels is measured. */
 int ff_debug_copy(const void *src, void *dst, size_t bytes, void *stream);
 
+/* Measured ceilings, on the default (null) stream: a register-resident loop of independent bf16
+ * 32x32x16 MFMAs, `iters` rounds of 8 per wavefront, four wavefronts per compute unit, with no memory
+ * traffic (*flops, a host pointer, receives the flops the launch performs); and a streaming read of
+ * `bytes` (a multiple of 16) from `src` (device, 16-byte aligned) with 16-byte loads, eight in flight
+ * per thread.  Timed by the caller, they give what the chip sustains next to the published peaks. */
+int ff_debug_mfma_loop(int64_t iters, double *flops);
+int ff_debug_stream_read(const void *src, size_t bytes);
+
 /* Tile shape of the tiled variants for later calls: tile = 0 (automatic), 64, 128 or 256;
  * wg_per_cu = 0 (automatic), 1 (a persistent grid of one workgroup per compute unit) or 2 (two,
  * not with 256-tiles).  The automatic choice is the fastest on every measured shape; the other

@@ -22,7 +22,7 @@ EXPORTS = [
     "ff_metric_selection", "ff_metric_select_host",
     "ff_workspace_bytes", "ff_set_workspace", "ff_check_device",
     "ff_status_string", "ff_version", "ff_last_variant", "ff_debug_linear",
-    "ff_debug_force_variant", "ff_debug_force_tile", "ff_debug_copy", "ff_debug_set_wait_limit_us", "ff_debug_expect_extra_arrivals",
+    "ff_debug_force_variant", "ff_debug_force_tile", "ff_debug_copy", "ff_debug_mfma_loop", "ff_debug_stream_read", "ff_debug_set_wait_limit_us", "ff_debug_expect_extra_arrivals",
 ]
 
 _lib = None
@@ -75,6 +75,10 @@ def load() -> ctypes.CDLL:
         lib.ff_debug_force_variant.argtypes = [ci]
         lib.ff_debug_copy.restype = ci
         lib.ff_debug_copy.argtypes = [vp, vp, ctypes.c_size_t, vp]
+        lib.ff_debug_mfma_loop.restype = ci
+        lib.ff_debug_mfma_loop.argtypes = [i64, ctypes.POINTER(ctypes.c_double)]
+        lib.ff_debug_stream_read.restype = ci
+        lib.ff_debug_stream_read.argtypes = [vp, ctypes.c_size_t]
         lib.ff_debug_force_tile.restype = ci
         lib.ff_debug_force_tile.argtypes = [ci, ci]
         lib.ff_debug_set_wait_limit_us.restype = ci
@@ -155,6 +159,25 @@ def ff_debug_copy(src: torch.Tensor, dst: torch.Tensor, stream=None) -> None:
         rc = load().ff_debug_copy(_ptr(src), _ptr(dst), nbytes, _stream(stream))
     if rc != FF_OK:
         raise FFError(rc)
+
+
+def ff_debug_mfma_loop(iters: int) -> float:
+    """Launches the MFMA-only loop on the null stream of the current device; returns its flop count."""
+    flops = ctypes.c_double(0.0)
+    rc = load().ff_debug_mfma_loop(int(iters), ctypes.byref(flops))
+    if rc != FF_OK:
+        raise FFError(rc)
+    return float(flops.value)
+
+
+def ff_debug_stream_read(src: torch.Tensor) -> int:
+    """Launches the streaming-read kernel over src on the null stream; returns the bytes read."""
+    nbytes = src.numel() * src.element_size()
+    with torch.cuda.device(src.device):
+        rc = load().ff_debug_stream_read(_ptr(src), nbytes)
+    if rc != FF_OK:
+        raise FFError(rc)
+    return nbytes
 
 
 def ff_debug_force_tile(tile: int, wg_per_cu: int = 0) -> None:

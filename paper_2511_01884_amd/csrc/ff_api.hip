@@ -638,6 +638,47 @@ int ff_debug_copy(const void *src, void *dst, size_t bytes, void *stream)
     return FF_OK;
 }
 
+int ff_debug_mfma_loop(int64_t iters, double *flops)
+{
+    if (!flops)
+        return FF_ERR_NULL;
+    if (iters <= 0 || iters > (int64_t)1 << 32)
+        return FF_ERR_SHAPE;
+    std::lock_guard<std::mutex> lock(g_mutex);
+    DeviceState *st = current_device_state();
+    if (!st)
+        return FF_ERR_LAUNCH;
+    // the kernel's per-thread results go to the workspace (they only keep the loop alive)
+    const int rc = prepare_workspace(*st, kCtrlBytes + (size_t)st->num_cus * 256 * sizeof(float), nullptr);
+    if (rc != FF_OK)
+        return rc;
+    float *sink = reinterpret_cast<float *>(static_cast<char *>(st->ws) + kCtrlBytes);
+    if (launch_mfma_loop(iters, sink, st->num_cus, nullptr, flops) != hipSuccess)
+        return FF_ERR_LAUNCH;
+    return FF_OK;
+}
+
+int ff_debug_stream_read(const void *src, size_t bytes)
+{
+    if (!src)
+        return FF_ERR_NULL;
+    if (misaligned(src))
+        return FF_ERR_ALIGN;
+    if (bytes % 16 != 0)
+        return FF_ERR_UNSUPPORTED;
+    std::lock_guard<std::mutex> lock(g_mutex);
+    DeviceState *st = current_device_state();
+    if (!st)
+        return FF_ERR_LAUNCH;
+    const int rc = prepare_workspace(*st, kCtrlBytes + (size_t)st->num_cus * 2 * 256 * sizeof(unsigned), nullptr);
+    if (rc != FF_OK)
+        return rc;
+    unsigned *sink = reinterpret_cast<unsigned *>(static_cast<char *>(st->ws) + kCtrlBytes);
+    if (launch_stream_read(src, bytes, sink, st->num_cus, nullptr) != hipSuccess)
+        return FF_ERR_LAUNCH;
+    return FF_OK;
+}
+
 int ff_debug_expect_extra_arrivals(int count)
 {
     if (count < 0 || count > 1024)

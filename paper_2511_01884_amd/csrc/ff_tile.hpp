@@ -85,6 +85,8 @@ struct XentParams {
 };
 
 hipError_t launch_copy_kernel(const void *src, void *dst, size_t bytes, int num_cus, hipStream_t stream);
+hipError_t launch_mfma_loop(long long iters, float *sink, int num_cus, hipStream_t stream, double *flops);
+hipError_t launch_stream_read(const void *src, size_t bytes, unsigned *sink, int num_cus, hipStream_t stream);
 
 // profiling-metric selection: device correlations, host selection
 hipError_t launch_pearson(const double *values, const double *runtime, double *r, int n, int V, int J,
