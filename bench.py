@@ -121,7 +121,10 @@ def main() -> int:
     ap.add_argument("--no-eager", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="target CPU time of the oracle sample")
     ap.add_argument("--no-extras", action="store_true",
-                    help="skip the batch-median, cache-warm and sustained-ceiling figures")
+                    help="skip the batch-median and sustained-ceiling figures")
+    ap.add_argument("--cache-warm", action="store_true",
+                    help="also time launches on a single buffer set (not in the default run, so that every "
+                         "launch of the default command has the rotating-buffer duration)")
     ap.add_argument("--print-source-hash", action="store_true", help="print the kernel source hash and exit")
     args = ap.parse_args()
     if args.print_source_hash:
@@ -209,7 +212,8 @@ def main() -> int:
     if not args.no_extras:
         launches = 100 if ms_kernel < 0.5 else 20
         roof["batch_median_ms"] = batch_median_ms(torch, step, launches)
-        roof["cache_warm_ms"] = batch_median_ms(torch, lambda i: step(0), launches, 3)   # one buffer set only
+        if args.cache_warm:   # one buffer set only: inputs stay in the Infinity Cache
+            roof["cache_warm_ms"] = batch_median_ms(torch, lambda i: step(0), launches, 3)
         if wl.dtype == "bf16" or hbm_bound:
             roof["sustained"] = sustained_ceiling(torch, B, roof["bound"])
             roof["frac_of_sustained"] = roof["achieved"] / roof["sustained"]["value"]
