@@ -112,7 +112,7 @@ def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
-    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=200)
     ap.add_argument("--workload", default="cfg1",
                     help="cfg0..cfg4 (default: cfg1, the metric's workload), f32_4096, copy (counter calibration), rowmean "
                          "(second fused chain: Linear, subtract, row-mean, GELU, residual add; bf16 4096^3), or xent "
