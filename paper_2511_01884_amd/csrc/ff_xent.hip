@@ -94,6 +94,34 @@ __device__ __forceinline__ void fold(float &m, float &s, const float (&f)[VEC])
     m = mn;
 }
 
+// Fold a whole batch of chunks with one rescale: the batch's maximum first, then every element's
+// exponential against it (per-chunk sums, added in chunk order).  Against folding chunk by chunk this
+// saves one exponential and a few selects per chunk, which matters for bf16 rows: they carry twice the
+// elements per byte and sit at the vector-ALU limit.
+template <int VEC>
+__device__ __forceinline__ void fold_batch(float &m, float &s, const float (&f)[kInFlight][VEC])
+{
+    float bm = f[0][0];
+#pragma unroll
+    for (int u = 0; u < kInFlight; ++u)
+#pragma unroll
+        for (int e = 0; e < VEC; ++e)
+            bm = fmaxf(bm, f[u][e]);
+    const float mn = fmaxf(m, bm);
+    const float ref = ref_of(mn);
+    float add = 0.0f;
+#pragma unroll
+    for (int u = 0; u < kInFlight; ++u) {
+        float part = 0.0f;
+#pragma unroll
+        for (int e = 0; e < VEC; ++e)
+            part += exp2_hw((f[u][e] - ref) * kLog2e);
+        add += part;
+    }
+    s = fmaf(s, exp2_hw((m - ref) * kLog2e), add);
+    m = mn;
+}
+
 // ROWT threads share a row: 64 (a wavefront per row, four rows per workgroup) or 256 (the
 // workgroup per row).  VEC = elements per load: 16 bytes' worth, or 1 when C is not a multiple
 // of that.
@@ -126,12 +154,11 @@ __global__ __launch_bounds__(kThreads) void xent_kernel(XentParams p)
 #pragma unroll
             for (int u = 0; u < kInFlight; ++u)
                 c[u].load(row + (size_t)(ch + u * ROWT) * VEC);
+            float f[kInFlight][VEC];
 #pragma unroll
-            for (int u = 0; u < kInFlight; ++u) {
-                float f[VEC];
-                c[u].get(f);
-                fold<VEC>(m, s, f);
-            }
+            for (int u = 0; u < kInFlight; ++u)
+                c[u].get(f[u]);
+            fold_batch<VEC>(m, s, f);
         }
         // the rest of the row, one chunk at a time
         for (; ch < nchunks; ch += ROWT) {
