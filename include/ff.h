@@ -38,9 +38,14 @@
  *   - Scratch memory ("workspace") holds per-tile row statistics and arrival
  *     counters (and, for the two-pass variant only, an fp32 copy of G).  If no
  *     workspace is bound the library allocates one per device on first use and
- *     grows it when needed (growing synchronises the device).  Calls that share
- *     a workspace must not overlap in time: use one stream, or bind distinct
- *     workspaces serially.
+ *     grows it when needed (growing synchronises the device).  Once a workspace
+ *     that is large enough exists, a call allocates nothing, synchronises
+ *     nothing and issues nothing but its kernels, so every call, the first
+ *     included, can be recorded into a HIP graph; a call that would have to
+ *     allocate or grow the library's own workspace while its stream is being
+ *     captured returns FF_ERR_WORKSPACE instead (bind a workspace, or make one
+ *     call of that shape, before capturing).  Calls that share a workspace must
+ *     not overlap in time: use one stream, or bind distinct workspaces serially.
  */
 #ifndef FF_H
 #define FF_H
@@ -166,9 +171,11 @@ size_t ff_workspace_bytes(int64_t M, int64_t K, int64_t N, int dtype);
 /*
  * Bind caller-owned device memory (256-byte aligned) as the workspace of the
  * current device, or unbind with (NULL, 0), after which the library allocates
- * its own again.  The first call after binding clears the control region of the
- * workspace with hipMemsetAsync on that call's stream.  The memory must stay
- * valid until unbound and all work using it has completed.
+ * its own again.  The call clears the control region (the first MiB) of the
+ * memory itself, synchronously, and synchronises the device; it must not be
+ * made while a stream is being captured, and no work that uses the previous
+ * workspace may be in flight.  The memory must stay valid until unbound and all
+ * work using it has completed.
  */
 int ff_set_workspace(void *dev_ptr, size_t bytes);
 
@@ -220,12 +227,33 @@ int ff_debug_copy(const void *src, void *dst, size_t bytes, void *stream);
 int ff_debug_mfma_loop(int64_t iters, double *flops);
 int ff_debug_stream_read(const void *src, size_t bytes);
 
-/* Tile shape of the tiled variants for later calls: tile = 0 (automatic), 64, 128 or 256;
- * wg_per_cu = 0 (automatic), 1 (a persistent grid of one workgroup per compute unit) or 2 (two,
- * not with 256-tiles).  The automatic choice is the fastest on every measured shape; the other
- * shapes exist as distinct kernels of the same operator for the profiling-metric study and
- * for tests.  FF_ERR_UNSUPPORTED for any other combination. */
+/* Tile shape of the tiled variants for later calls: tile = 0 (automatic), 64, 128 or 256 (columns);
+ * wg_per_cu = 0 (automatic), 1 (a persistent grid of one workgroup per compute unit) or 2 (two).
+ * (256, 0 or 1) is the 256 x 256 tile, one workgroup per compute unit; (256, 2) the 256-column x
+ * 128-row tile, two per compute unit.  The shapes the automatic plan does not pick exist as distinct
+ * kernels of the same operator for the profiling-metric study and for tests.  FF_ERR_UNSUPPORTED
+ * for any other combination. */
 int ff_debug_force_tile(int tile, int wg_per_cu);
+
+/* Wavefronts per workgroup of the 256 x 256 tile for later calls: 0 (automatic), 4 (2 x 2
+ * wavefronts of 4 x 4 MFMA blocks) or 8 (2 x 4 wavefronts of 4 x 2 blocks).  While 4 or 8 is forced,
+ * a call whose plan uses 256-column tiles runs the 256 x 256 tile with that many wavefronts, and a
+ * call whose plan uses a narrower tile returns FF_ERR_UNSUPPORTED. */
+int ff_debug_force_waves(int waves);
+
+/* Start delay, in microseconds (0..1000, default 12), of the second workgroup of every compute unit
+ * in launches of the 256-column x 128-row tile over a full grid: with it, the epilogue of one
+ * workgroup falls into the K loop of the other from the first tile on. */
+int ff_debug_set_stagger_us(int microseconds);
+
+/* Phase timestamps of the tiled kernels.  Binds `bytes` of device memory (8-byte aligned; NULL
+ * unbinds) for the current device.  While bound, thread 0 of every workgroup of a tiled launch
+ * writes, for each of its tiles that fits, 16 uint64 words at
+ * [(round * grid + workgroup) * 16]: words 0..6 the 100 MHz wall clock at tile start, first K slab
+ * in LDS, end of the K loop, row statistics published, other tiles of the rows arrived, statistics
+ * merged, stores issued; words 8, 9 the shader clock at the start and end of the K loop.  The
+ * timings a launch reports this way differ from an untimed launch by the stores themselves. */
+int ff_debug_set_timeline(void *dev_ptr, size_t bytes);
 
 /* Upper bound, in microseconds, a workgroup waits for the other tiles of its
  * rows before it gives up and flags FF_ERR_DEVICE (default 2,000,000). */

@@ -22,7 +22,7 @@ EXPORTS = [
     "ff_metric_selection", "ff_metric_select_host",
     "ff_workspace_bytes", "ff_set_workspace", "ff_check_device",
     "ff_status_string", "ff_version", "ff_last_variant", "ff_debug_linear",
-    "ff_debug_force_variant", "ff_debug_force_tile", "ff_debug_copy", "ff_debug_mfma_loop", "ff_debug_stream_read", "ff_debug_set_wait_limit_us", "ff_debug_expect_extra_arrivals",
+    "ff_debug_force_variant", "ff_debug_force_tile", "ff_debug_force_waves", "ff_debug_set_stagger_us", "ff_debug_set_timeline", "ff_debug_copy", "ff_debug_mfma_loop", "ff_debug_stream_read", "ff_debug_set_wait_limit_us", "ff_debug_expect_extra_arrivals",
 ]
 
 _lib = None
@@ -81,6 +81,12 @@ def load() -> ctypes.CDLL:
         lib.ff_debug_stream_read.argtypes = [vp, ctypes.c_size_t]
         lib.ff_debug_force_tile.restype = ci
         lib.ff_debug_force_tile.argtypes = [ci, ci]
+        lib.ff_debug_force_waves.restype = ci
+        lib.ff_debug_force_waves.argtypes = [ci]
+        lib.ff_debug_set_stagger_us.restype = ci
+        lib.ff_debug_set_stagger_us.argtypes = [ci]
+        lib.ff_debug_set_timeline.restype = ci
+        lib.ff_debug_set_timeline.argtypes = [vp, ctypes.c_size_t]
         lib.ff_debug_set_wait_limit_us.restype = ci
         lib.ff_debug_set_wait_limit_us.argtypes = [i64]
         lib.ff_debug_expect_extra_arrivals.restype = ci
@@ -182,6 +188,29 @@ def ff_debug_stream_read(src: torch.Tensor) -> int:
 
 def ff_debug_force_tile(tile: int, wg_per_cu: int = 0) -> None:
     rc = load().ff_debug_force_tile(int(tile), int(wg_per_cu))
+    if rc != FF_OK:
+        raise FFError(rc)
+
+
+def ff_debug_force_waves(waves: int) -> None:
+    rc = load().ff_debug_force_waves(int(waves))
+    if rc != FF_OK:
+        raise FFError(rc)
+
+
+def ff_debug_set_stagger_us(us: int) -> None:
+    rc = load().ff_debug_set_stagger_us(int(us))
+    if rc != FF_OK:
+        raise FFError(rc)
+
+
+def ff_debug_set_timeline(buf: Optional[torch.Tensor]) -> None:
+    """Binds a device tensor (any 8-byte dtype) for the tiled kernels' phase timestamps; None unbinds."""
+    if buf is None:
+        rc = load().ff_debug_set_timeline(None, 0)
+    else:
+        with torch.cuda.device(buf.device):
+            rc = load().ff_debug_set_timeline(ctypes.c_void_p(buf.data_ptr()), buf.numel() * buf.element_size())
     if rc != FF_OK:
         raise FFError(rc)
 

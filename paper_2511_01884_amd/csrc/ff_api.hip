@@ -18,10 +18,12 @@ struct DeviceState {
     bool probed = false;
     int num_cus = 256;
     long long ticks_per_us = 100;
-    void *ws = nullptr;       // bound or owned workspace
+    void *ws = nullptr;       // bound or owned workspace; its control region is zeroed when it is bound or allocated
     size_t ws_bytes = 0;
     bool ws_owned = false;
-    bool ws_clean = false;    // control region zeroed since (re)binding
+    unsigned long long *timeline = nullptr;  // test hook: phase timestamps of the tiled kernels
+    size_t timeline_bytes = 0;
+    signed char blocks_per_cu[2][kNumTileShapes][3] = {};  // cached occupancy answers [bf16][shape][mode], 0 = not asked
 };
 
 std::mutex g_mutex;
@@ -31,13 +33,17 @@ long long g_wait_limit_us = 2000000;
 int g_extra_arrivals = 0;
 int g_forced_tile = 0;        // 0 = automatic, else 64, 128 or 256
 int g_forced_wg_per_cu = 0;   // 0 = automatic (one workgroup per compute unit), else 1 or 2
+int g_forced_waves = 0;       // 0 = automatic, else 4 or 8 wavefronts per workgroup of the 256 x 256 tile
+int g_stagger_us = 12;        // start delay of the second workgroup per compute unit (256 x 128 tiles)
 thread_local int t_last_variant = 0;
 
 struct Plan {
     int variant = 0;
-    int tile = 0;      // BM = BN of the tiled variants
+    int shape = 0;     // a TileShape
+    int tile_m = 0, tile_n = 0;  // rows and columns of a tile
+    int stagger_us = 0;
     int NT = 0, RB = 0;
-    int grid = 0, rounds = 0, swz_sc = 0;
+    int grid = 0, rounds = 0, swz_sc_log2 = -1, nt_log2 = 0, grid_log2 = 0;
     int mt = 0, strips = 0;  // small-M
     size_t partial_off = 0, partial_bytes = 0;
     size_t g_off = 0, g_bytes = 0;
@@ -63,8 +69,22 @@ int validate_shape(int64_t M, int64_t K, int64_t N, int dtype)
 }
 
 // Decides variant, tile size, grid and workspace layout for a shape.
-int make_plan(int64_t M, int64_t K, int64_t N, int dtype, int num_cus, int forced, bool linear_only,
-              Plan &pl)
+// Workgroups of the chosen tile kernel that fit a compute unit at once, asked of the runtime once per
+// kernel and device; 0 when unknown.
+int resident_blocks_per_cu(DeviceState *st, bool bf16, int shape, int mode)
+{
+    if (st == nullptr)
+        return 0;
+    signed char &slot = st->blocks_per_cu[bf16 ? 1 : 0][shape][mode];
+    if (slot == 0) {
+        const int n = tile_kernel_blocks_per_cu(bf16, shape, mode);
+        slot = (signed char)(n <= 0 ? -1 : (n > 100 ? 100 : n));
+    }
+    return slot < 0 ? 0 : slot;
+}
+
+int make_plan(int64_t M, int64_t K, int64_t N, int dtype, int num_cus, DeviceState *st, int forced,
+              bool linear_only, Plan &pl)
 {
     (void)K;
     const bool bf16 = dtype == FF_BF16;
@@ -90,24 +110,51 @@ int make_plan(int64_t M, int64_t K, int64_t N, int dtype, int num_cus, int force
         return FF_OK;
     }
 
-    // tiled variants: 256x256 tiles unless they would fill at most half of the compute units (then the
-    // 128-tiles, two per compute unit, finish in one round and are faster; measured); problems of at
-    // most a quarter of the compute units' worth of 128-tiles take 64-tiles, which spread them further
+    // Tiled variants.  Large problems take 256 x 256 tiles, one workgroup per compute unit: eight
+    // wavefronts when the problem is a single round of tiles (their stores drain faster), four when
+    // a workgroup walks several tiles (measured: 4096^3 114.6 against 116.6 us; 65536 x 1024 x 1024
+    // 167.6 against 165.2 us; 8192 x 4096 x 16384 994 against 969 us).  Problems of at most half the
+    // compute units' worth of 256-tiles take 128-tiles, two per compute unit, which finish in one
+    // round; at most a quarter of the compute units' worth of 128-tiles: 64-tiles, which spread them
+    // further.  The 256-column x 128-row tile, two workgroups per compute unit, is never chosen: the
+    // overlap of one workgroup's epilogue with the other's K loop does not pay for the 1.5 times larger
+    // L2 -> LDS traffic per flop (4096^3: 148 us).
     const int64_t tiles256 = ((M + 255) / 256) * ((N + 255) / 256);
     const int64_t tiles128 = ((M + 127) / 128) * ((N + 127) / 128);
-    pl.tile = tiles256 * 2 > num_cus ? 256 : (tiles128 * 4 > num_cus ? 128 : 64);
-    if (g_forced_tile != 0)
-        pl.tile = g_forced_tile;
-    const int64_t RB = (M + pl.tile - 1) / pl.tile;
-    const int64_t NT = (N + pl.tile - 1) / pl.tile;
+    pl.shape = tiles256 * 2 > num_cus ? (tiles256 <= num_cus ? kTile256W8 : kTile256)
+                                      : (tiles128 * 4 > num_cus ? kTile128 : kTile64);
+    if (g_forced_tile != 0) {
+        pl.shape = g_forced_tile == 64 ? kTile64 : (g_forced_tile == 128 ? kTile128 : kTile256);
+        if (g_forced_tile == 256 && g_forced_wg_per_cu == 2)
+            pl.shape = kTile256x128;
+    }
+    if (g_forced_waves != 0) {
+        if (tile_shape_cols(pl.shape) != 256)
+            return FF_ERR_UNSUPPORTED;
+        pl.shape = g_forced_waves == 8 ? kTile256W8 : kTile256;
+    }
+    pl.tile_m = tile_shape_rows(pl.shape);
+    pl.tile_n = tile_shape_cols(pl.shape);
+    const int64_t RB = (M + pl.tile_m - 1) / pl.tile_m;
+    const int64_t NT = (N + pl.tile_n - 1) / pl.tile_n;
     if (RB > kMaxRowBlocks - 1 || RB * NT > (int64_t)1 << 30)  // the last counter pair belongs to the cross-entropy kernel
         return FF_ERR_SHAPE;
     pl.RB = (int)RB;
     pl.NT = (int)NT;
     const int64_t total = RB * NT;
-    // two 128-tiles fit a compute unit's LDS and registers at once (measured faster than one on every
-    // shape); a 256-tile takes all of both
-    const int64_t grid_cap = (int64_t)num_cus * ((pl.tile != 256 && g_forced_wg_per_cu != 1) ? 2 : 1);
+    // workgroups per compute unit: a 256 x 256 tile takes a whole unit's LDS and registers, the other
+    // shapes half or less
+    int per_cu = (pl.shape == kTile256 || pl.shape == kTile256W8) ? 1 : 2;
+    if (g_forced_wg_per_cu == 1)
+        per_cu = 1;
+    // The fused kernel's workgroups wait for one another inside the launch: never launch more of them
+    // than the runtime says are resident at once.
+    if (variant != FF_VARIANT_TILED_TWOPASS && !linear_only) {
+        const int fit = resident_blocks_per_cu(st, bf16, pl.shape, kFused);
+        if (fit > 0 && per_cu > fit)
+            per_cu = fit;
+    }
+    const int64_t grid_cap = (int64_t)num_cus * per_cu;
     pl.grid = (int)(total < grid_cap ? total : grid_cap);
     pl.rounds = (int)((total + pl.grid - 1) / pl.grid);
     const bool fused_ok = NT <= pl.grid;
@@ -118,16 +165,27 @@ int make_plan(int64_t M, int64_t K, int64_t N, int dtype, int num_cus, int force
     if (variant != FF_VARIANT_TILED_FUSED && variant != FF_VARIANT_TILED_TWOPASS)
         return FF_ERR_UNSUPPORTED;
     pl.variant = variant;
-    // XCD-aware tile order: needs 8 XCDs x 32 workgroups and NT dividing the grid
-    pl.swz_sc = 0;
-    if (pl.grid == 256 && NT <= 256 && (256 % NT) == 0) {
+    // XCD-aware tile order: needs 8 XCDs x 32 or 64 workgroups and NT a power of two that divides
+    // the grid (the kernel's index arithmetic is then all shifts)
+    pl.swz_sc_log2 = -1;
+    pl.nt_log2 = 0;
+    pl.grid_log2 = 0;
+    if ((pl.grid == 256 || pl.grid == 512) && NT <= pl.grid && (NT & (NT - 1)) == 0) {
         int sc = (int)(NT / 8 > 8 ? NT / 8 : 8);
         if (sc > NT)
             sc = (int)NT;
-        pl.swz_sc = sc;
+        while ((1 << pl.nt_log2) < NT)
+            ++pl.nt_log2;
+        while ((1 << pl.grid_log2) < pl.grid)
+            ++pl.grid_log2;
+        pl.swz_sc_log2 = 0;
+        while ((1 << pl.swz_sc_log2) < sc)
+            ++pl.swz_sc_log2;
     }
+    // start delay of the second workgroup of every compute unit (256 x 128 tiles, full grid only)
+    pl.stagger_us = (pl.shape == kTile256x128 && per_cu == 2 && pl.grid == 2 * num_cus) ? g_stagger_us : 0;
     pl.partial_off = kCtrlBytes;
-    pl.partial_bytes = round_up((size_t)total * pl.tile * sizeof(float) * 2, 256);
+    pl.partial_bytes = round_up((size_t)total * pl.tile_m * sizeof(float) * 2, 256);
     pl.g_off = pl.partial_off + pl.partial_bytes;
     pl.g_bytes = (variant == FF_VARIANT_TILED_TWOPASS && !linear_only)
                      ? round_up((size_t)M * (size_t)N * sizeof(float), 256)
@@ -158,35 +216,46 @@ DeviceState *current_device_state(int *dev_out = nullptr)
     return &st;
 }
 
-// Makes sure a workspace of at least `bytes` exists and its control region is zero.
+// Makes sure a workspace of at least `bytes` exists.  The control region of a workspace is zeroed,
+// synchronously, when it is allocated here or bound by ff_set_workspace, never on a caller's stream;
+// the kernels leave it zero behind them.  Allocating, freeing and synchronising are illegal while a
+// stream is being captured, so a call that would have to grow the library's own workspace during a
+// capture is refused instead.
 int prepare_workspace(DeviceState &st, size_t bytes, hipStream_t stream)
 {
-    if (st.ws == nullptr || (st.ws_owned && st.ws_bytes < bytes)) {
-        if (st.ws != nullptr) {
-            (void)hipDeviceSynchronize();
-            (void)hipFree(st.ws);
-            st.ws = nullptr;
-        }
-        const size_t want = round_up(bytes + bytes / 4, 1 << 20);
-        if (hipMalloc(&st.ws, want) != hipSuccess) {
-            (void)hipGetLastError();
-            st.ws = nullptr;
-            st.ws_bytes = 0;
-            return FF_ERR_WORKSPACE;
-        }
-        st.ws_bytes = want;
-        st.ws_owned = true;
-        st.ws_clean = false;
-    }
-    if (st.ws_bytes < bytes)
+    if (st.ws != nullptr && st.ws_bytes >= bytes)
+        return FF_OK;
+    if (st.ws != nullptr && !st.ws_owned)
+        return FF_ERR_WORKSPACE;  // the caller's workspace is too small
+    hipStreamCaptureStatus capture = hipStreamCaptureStatusNone;
+    if (hipStreamIsCapturing(stream, &capture) != hipSuccess) {
+        (void)hipGetLastError();
         return FF_ERR_WORKSPACE;
-    if (!st.ws_clean) {
-        if (hipMemsetAsync(st.ws, 0, kCtrlBytes, stream) != hipSuccess) {
+    }
+    if (capture != hipStreamCaptureStatusNone)
+        return FF_ERR_WORKSPACE;
+    if (st.ws != nullptr) {
+        if (hipDeviceSynchronize() != hipSuccess || hipFree(st.ws) != hipSuccess) {
             (void)hipGetLastError();
             return FF_ERR_LAUNCH;
         }
-        st.ws_clean = true;
+        st.ws = nullptr;
+        st.ws_bytes = 0;
     }
+    const size_t want = round_up(bytes + bytes / 4, 1 << 20);
+    void *mem = nullptr;
+    if (hipMalloc(&mem, want) != hipSuccess) {
+        (void)hipGetLastError();
+        return FF_ERR_WORKSPACE;
+    }
+    if (hipMemset(mem, 0, kCtrlBytes) != hipSuccess || hipDeviceSynchronize() != hipSuccess) {
+        (void)hipGetLastError();
+        (void)hipFree(mem);
+        return FF_ERR_LAUNCH;
+    }
+    st.ws = mem;
+    st.ws_bytes = want;
+    st.ws_owned = true;
     return FF_OK;
 }
 
@@ -210,7 +279,7 @@ int run(const void *X, const void *W, const void *b, const void *gamma, const vo
     if (!st)
         return FF_ERR_LAUNCH;
     Plan pl;
-    rc = make_plan(M, K, N, dtype, st->num_cus, g_forced_variant, linear_only, pl);
+    rc = make_plan(M, K, N, dtype, st->num_cus, st, g_forced_variant, linear_only, pl);
     if (rc != FF_OK)
         return rc;
     rc = prepare_workspace(*st, pl.total_bytes, stream);
@@ -248,17 +317,27 @@ int run(const void *X, const void *W, const void *b, const void *gamma, const vo
     p.err = err;
     p.eps = eps;
     p.M = (int)M; p.K = (int)K; p.N = (int)N;
-    p.NT = pl.NT; p.RB = pl.RB; p.rounds = pl.rounds; p.swz_sc = pl.swz_sc;
+    p.NT = pl.NT; p.RB = pl.RB; p.rounds = pl.rounds; p.swz_sc_log2 = pl.swz_sc_log2; p.nt_log2 = pl.nt_log2;
+    p.grid_log2 = pl.grid_log2;
+    p.stagger_ticks = (long long)pl.stagger_us * st->ticks_per_us;
     p.extra_arrivals = g_extra_arrivals;
     p.wait_ticks = wait_ticks;
+    p.timeline = nullptr;
+    p.timeline_rounds = 0;
+    if (st->timeline != nullptr) {
+        const size_t per_round = (size_t)pl.grid * kTimelineSlots * sizeof(unsigned long long);
+        const size_t rounds = st->timeline_bytes / per_round;
+        p.timeline = rounds > 0 ? st->timeline : nullptr;
+        p.timeline_rounds = (int)(rounds < (size_t)pl.rounds ? rounds : (size_t)pl.rounds);
+    }
     const int mode = linear_only ? kLinearOnly
                                  : (pl.variant == FF_VARIANT_TILED_FUSED ? kFused : kTwoPass);
-    if (launch_tile_kernel(bf16, pl.tile, mode, p, pl.grid, stream) != hipSuccess)
+    if (launch_tile_kernel(bf16, pl.shape, mode, p, pl.grid, stream) != hipSuccess)
         return FF_ERR_LAUNCH;
     if (mode == kTwoPass) {
         FinalizeParams f{};
         f.G = p.F; f.partials = p.partials; f.gamma = gamma; f.beta = beta; f.Y = Y;
-        f.eps = eps; f.M = (int)M; f.N = (int)N; f.NT = pl.NT; f.BM = pl.tile; f.BN = pl.tile;
+        f.eps = eps; f.M = (int)M; f.N = (int)N; f.NT = pl.NT; f.BM = pl.tile_m; f.BN = pl.tile_n;
         if (launch_finalize_kernel(bf16, f, stream) != hipSuccess)
             return FF_ERR_LAUNCH;
     }
@@ -532,7 +611,7 @@ size_t ff_workspace_bytes(int64_t M, int64_t K, int64_t N, int dtype)
     DeviceState *st = current_device_state();
     const int num_cus = st ? st->num_cus : 256;
     Plan pl;
-    if (make_plan(M, K, N, dtype, num_cus, g_forced_variant, false, pl) != FF_OK)
+    if (make_plan(M, K, N, dtype, num_cus, st, g_forced_variant, false, pl) != FF_OK)
         return 0;
     return pl.total_bytes;
 }
@@ -547,14 +626,20 @@ int ff_set_workspace(void *dev_ptr, size_t bytes)
         return FF_ERR_ALIGN;
     if (dev_ptr != nullptr && bytes < kCtrlBytes)
         return FF_ERR_WORKSPACE;
+    if (dev_ptr != nullptr &&
+        (hipMemset(dev_ptr, 0, kCtrlBytes) != hipSuccess || hipDeviceSynchronize() != hipSuccess)) {
+        (void)hipGetLastError();
+        return FF_ERR_LAUNCH;  // the old binding stays
+    }
     if (st->ws != nullptr && st->ws_owned) {
-        (void)hipDeviceSynchronize();
-        (void)hipFree(st->ws);
+        if (hipDeviceSynchronize() != hipSuccess || hipFree(st->ws) != hipSuccess) {
+            (void)hipGetLastError();
+            return FF_ERR_LAUNCH;
+        }
     }
     st->ws = dev_ptr;
     st->ws_bytes = dev_ptr ? bytes : 0;
     st->ws_owned = false;
-    st->ws_clean = false;
     return FF_OK;
 }
 
@@ -568,7 +653,7 @@ int ff_check_device(void *stream)
         (void)hipGetLastError();
         return FF_ERR_LAUNCH;
     }
-    if (st->ws == nullptr || !st->ws_clean)
+    if (st->ws == nullptr)
         return FF_OK;
     unsigned flag = 0;
     if (hipMemcpy(&flag, st->ws, sizeof(flag), hipMemcpyDeviceToHost) != hipSuccess) {
@@ -613,12 +698,42 @@ int ff_debug_force_variant(int variant)
 
 int ff_debug_force_tile(int tile, int wg_per_cu)
 {
-    if ((tile != 0 && tile != 64 && tile != 128 && tile != 256) || wg_per_cu < 0 || wg_per_cu > 2 ||
-        (wg_per_cu == 2 && tile != 128 && tile != 64))
+    if ((tile != 0 && tile != 64 && tile != 128 && tile != 256) || wg_per_cu < 0 || wg_per_cu > 2)
         return FF_ERR_UNSUPPORTED;
     std::lock_guard<std::mutex> lock(g_mutex);
     g_forced_tile = tile;
     g_forced_wg_per_cu = wg_per_cu;
+    return FF_OK;
+}
+
+int ff_debug_force_waves(int waves)
+{
+    if (waves != 0 && waves != 4 && waves != 8)
+        return FF_ERR_UNSUPPORTED;
+    std::lock_guard<std::mutex> lock(g_mutex);
+    g_forced_waves = waves;
+    return FF_OK;
+}
+
+int ff_debug_set_stagger_us(int microseconds)
+{
+    if (microseconds < 0 || microseconds > 1000)
+        return FF_ERR_SHAPE;
+    std::lock_guard<std::mutex> lock(g_mutex);
+    g_stagger_us = microseconds;
+    return FF_OK;
+}
+
+int ff_debug_set_timeline(void *dev_ptr, size_t bytes)
+{
+    if (dev_ptr != nullptr && (reinterpret_cast<uintptr_t>(dev_ptr) & 7u) != 0)
+        return FF_ERR_ALIGN;
+    std::lock_guard<std::mutex> lock(g_mutex);
+    DeviceState *st = current_device_state();
+    if (!st)
+        return FF_ERR_LAUNCH;
+    st->timeline = static_cast<unsigned long long *>(dev_ptr);
+    st->timeline_bytes = dev_ptr ? bytes : 0;
     return FF_OK;
 }
 

@@ -27,9 +27,6 @@ namespace ff {
 
 namespace {
 
-constexpr int kWavesN = 2;
-constexpr int kWavesM = 2;
-constexpr int kThreads = 64 * kWavesN * kWavesM;
 constexpr int kRowBytes = 128;  // bytes of one tile row per K slab (8 chunks of 16 B)
 constexpr int kChunksPerRow = kRowBytes / 16;
 constexpr int kStepsPerSlab = kChunksPerRow / 2;  // a k-step consumes two chunks (one per lane half)
@@ -89,6 +86,28 @@ __device__ __forceinline__ void pin_order(floatx16 &c0, floatx16 &c1)
     asm volatile("" : "+a"(c0), "+a"(c1) : : "memory");
 }
 
+// The lane index, computed where it is asked for: the compiler can neither move the computation out
+// of a loop nor keep its result across one (values that the K loop does not use would have to be
+// carried across it in scratch memory).
+__device__ __forceinline__ int opaque_lane()
+{
+    int l;
+    asm volatile("v_mbcnt_lo_u32_b32 %0, -1, 0\n\tv_mbcnt_hi_u32_b32 %0, -1, %0" : "=v"(l));
+    return l;
+}
+// The value of a uniform integer, hidden from the optimiser in the same way.
+__device__ __forceinline__ int opaque_uniform(int v)
+{
+    int r;
+    asm volatile("s_mov_b32 %0, %1" : "=s"(r) : "s"(v));
+    return r;
+}
+// The other half-wave's value (lane ^ 32), through the LDS crossbar.
+__device__ __forceinline__ float swap_halves(float v, int lane)
+{
+    return __int_as_float(__builtin_amdgcn_ds_bpermute((lane ^ 32) << 2, __float_as_int(v)));
+}
+
 // LDS placement of 16-byte chunk `c` (0..7) of tile row `row`: chunks are XORed
 // with row bits so that the consecutive rows a fragment read touches per pass
 // (stride 128 B) spread over all banks, for 8-lane and for 16-lane passes.
@@ -100,20 +119,43 @@ template <> struct MmaCount<float> { static constexpr int value = 4; };
 
 // RAGGED_N: N is not a multiple of the tile width, so the last tile of each row
 // masks the columns at or beyond N in the statistics (chosen on the host).
-template <typename T, int WTN, int WTM, int MODE, bool RAGGED_N>
-__global__ __launch_bounds__(kThreads) void tile_kernel(const TileParams p)
+//
+// Wave layout: kWavesN x kWavesM wavefronts, each owning WTN x WTM MFMA blocks of 32 x 32.  The
+// 256-tile runs as 2 x 4 wavefronts of 4 x 2 blocks (two wavefronts per SIMD: 128 accumulator
+// registers each, and eight wavefronts keep twice as many loads in flight on the L2 -> LDS path
+// as four) or as 2 x 2 wavefronts of 4 x 4 blocks; the 128- and 64-tiles as 2 x 2 wavefronts, two
+// workgroups per compute unit (second launch bound: two wavefronts per SIMD must fit).
+//
+// PIPE selects how the K slabs reach the LDS.  kPipeDma: W and X slabs both by direct-to-LDS loads
+// into two stages (one workgroup per compute unit at 256 x 256; the whole LDS).  kPipeXReg: the W
+// slab by direct-to-LDS loads into two stages, the X slab through registers into a single buffer
+// (loaded a slab ahead, written between two barriers once everyone has read the previous one).
+// That fits a 256-column x 128-row tile into half the LDS (2 x 32 KB + 16 KB), so that two
+// workgroups share a compute unit: while one is in its epilogue (vector ALU, exchange, stores) the
+// other's K loop keeps the matrix pipe busy, and each covers the other's barrier stalls.
+template <typename T, int kWavesN, int kWavesM, int WTN, int WTM, int MODE, bool RAGGED_N, int PIPE>
+__global__ __launch_bounds__(64 * kWavesN * kWavesM, (kWavesN * kWavesM * WTN * WTM <= 32) ? 2 : 1)
+void tile_kernel(const TileParams p)
 {
 #if defined(__HIP_DEVICE_COMPILE__)  // the body uses device-only types (buffer descriptors)
+    constexpr int kWaves = kWavesN * kWavesM;
+    constexpr int kThreads = 64 * kWaves;
     constexpr int BN = kWavesN * WTN * 32;
     constexpr int BM = kWavesM * WTM * 32;
     constexpr int kChunkElems = 16 / (int)sizeof(T);
     constexpr int kSlabElems = kRowBytes / (int)sizeof(T);
     constexpr int kABytes = BN * kRowBytes;
     constexpr int kBBytes = BM * kRowBytes;
+    // LDS placement of the slabs: W of slab s at (s % 2) * kWStride, X of slab s at kXBase + (s % 2) * kXStride
+    constexpr bool kXReg = PIPE == kPipeXReg;
     constexpr int kStageBytes = kABytes + kBBytes;
+    constexpr int kWStride = kXReg ? kABytes : kStageBytes;
+    constexpr int kXBase = kXReg ? kStages * kABytes : kABytes;
+    constexpr int kXStride = kXReg ? 0 : kStageBytes;
+    constexpr int kSlabLdsBytes = kXReg ? kStages * kABytes + kBBytes : kStages * kStageBytes;
     // direct-to-LDS instructions per wave per slab
-    constexpr int kDmaA = BN / kRowsPerDma / (kWavesN * kWavesM);
-    constexpr int kDmaB = BM / kRowsPerDma / (kWavesN * kWavesM);
+    constexpr int kDmaA = BN / kRowsPerDma / kWaves;
+    constexpr int kDmaB = BM / kRowsPerDma / kWaves;
     constexpr int kDmaPerSlab = kDmaA + kDmaB;
     // epilogue LDS regions (reuse the stage buffers)
     using OutT = typename std::conditional<MODE == kFused, T, float>::type;
@@ -123,54 +165,78 @@ __global__ __launch_bounds__(kThreads) void tile_kernel(const TileParams p)
     constexpr int kOffWst = kOffPrm + 3 * BN * 4;            // kWavesN * BM float2
     constexpr int kOffRst = kOffWst + kWavesN * BM * 8;      // BM float2
     constexpr int kOffOut = (kOffRst + BM * 8 + 1023) & ~1023;
-    constexpr int kEpiBytes = kOffOut + kWavesN * kWavesM * 32 * kOutPitch;
-    constexpr int kSmemBytes = (kStages * kStageBytes > kEpiBytes) ? kStages * kStageBytes : kEpiBytes;
+    constexpr int kEpiBytes = kOffOut + kWaves * 32 * kOutPitch;
+    constexpr int kSmemBytes = (kSlabLdsBytes > kEpiBytes) ? kSlabLdsBytes : kEpiBytes;
 
     __shared__ __attribute__((aligned(1024))) char smem[kSmemBytes];
 
-    const int tid = threadIdx.x;
-    const int lane = tid & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int wn = wave % kWavesN;
     const int wm = wave / kWavesN;
-    const int h = lane >> 5;
-    const int l32 = lane & 31;
 
-    const int M = p.M, N = p.N, K = p.K;
-    const int slabs = (K + kSlabElems - 1) / kSlabElems;
-    const bool k_ragged = (K % kSlabElems) != 0;
-    const size_t row_stride = (size_t)K * sizeof(T);
+    // Phase timestamps (test hook): when a timeline buffer is bound, thread 0 of every workgroup writes
+    // the wall clock at the phase boundaries of each of its first `timeline_rounds` tiles into
+    // timeline[(round * grid + workgroup) * kTimelineSlots + k].
+    int round = 0;
+    bool stamper = false;  // thread 0 of the workgroup, decided per tile
+    auto stamp = [&](int k) {
+        if (p.timeline != nullptr && stamper && round < p.timeline_rounds)
+            p.timeline[((size_t)round * gridDim.x + blockIdx.x) * kTimelineSlots + k] =
+                k < kTimelineCycleSlot ? wall_clock64() : clock64();
+    };
 
-    // fragment read offsets (bytes inside a stage); k-step s reads chunk (2s + h) ^ swizzle
-    const int frag_swz = swizzle_of_row(l32);
-    const int a_frag_base = (wn * WTN * 32 + l32) * kRowBytes;
-    const int b_frag_base = kABytes + (wm * WTM * 32 + l32) * kRowBytes;
-
-    // DMA lane geometry: lane -> (row within a 16-row group, stored chunk slot)
-    const int dma_r = lane / kChunksPerRow;
-    const int dma_cs = lane % kChunksPerRow;
+    // Two workgroups per compute unit started together would run their K loops and their epilogues
+    // in step; the second half of the grid starts late by about an epilogue's length instead, so
+    // that one workgroup's epilogue falls into the other's K loop from the first tile on.
+    if (p.stagger_ticks > 0 && blockIdx.x >= (gridDim.x >> 1)) {
+        const long long t0 = wall_clock64();
+        while (wall_clock64() - t0 < p.stagger_ticks)
+            __builtin_amdgcn_s_sleep(16);
+    }
 
     bool first_tile = true;
-    for (int t = blockIdx.x; t < p.rounds * (int)gridDim.x; t += gridDim.x) {
+    for (; round < p.rounds; ++round) {
         // ---- tile coordinates (XCD-aware order inside a round when enabled) ----
         int rb, cb;
-        if (p.swz_sc > 0) {
-            const int round = t / (int)gridDim.x;
+        if (p.swz_sc_log2 >= 0) {
+            // 8 XCDs x (grid / 8) workgroups, grid and NT powers of two: all quotients are shifts.
+            // XCD x takes a block of sr x sc tiles (sc = 1 << swz_sc_log2 columns, sr = grid / 8 / sc
+            // rows) of the round's (grid / NT) x NT tiles; the workgroups of the second half of the
+            // grid take the lower rows of their XCD's block.
             const int xcd = blockIdx.x & 7;
             const int slot = blockIdx.x >> 3;
-            const int sc = p.swz_sc, sr = 32 / sc;
-            const int across = p.NT / sc;
-            const int sbr = xcd / across, sbc = xcd % across;
-            rb = round * ((int)gridDim.x / p.NT) + sbr * sr + slot / sc;
-            cb = sbc * sc + slot % sc;
+            const int scl = p.swz_sc_log2;
+            const int across_log2 = p.nt_log2 - scl;
+            const int sbr = xcd >> across_log2, sbc = xcd & ((1 << across_log2) - 1);
+            rb = (round << (p.grid_log2 - p.nt_log2)) + (sbr << (p.grid_log2 - 3 - scl)) + (slot >> scl);
+            cb = (sbc << scl) + (slot & ((1 << scl) - 1));
         } else {
+            const int t = round * (int)gridDim.x + (int)blockIdx.x;
             rb = t / p.NT;
-            cb = t % p.NT;
+            cb = t - rb * p.NT;
         }
         if (rb >= p.RB)
             continue;  // uniform for the workgroup
+        // Everything derived from the lane index and from the shape is computed here, per tile, where
+        // it is used.
+        const int lane = opaque_lane();
+        const int M = opaque_uniform(p.M), N = opaque_uniform(p.N), K = opaque_uniform(p.K);
+        const int slabs = (K + kSlabElems - 1) / kSlabElems;
+        const bool k_ragged = (K % kSlabElems) != 0;
+        const size_t row_stride = (size_t)K * sizeof(T);
+        stamper = wave == 0 && lane == 0;
+        stamp(0);
         const int m0 = rb * BM;
         const int n0 = cb * BN;
+        const int h = lane >> 5;
+        const int l32 = lane & 31;
+        // fragment read offsets (bytes inside a stage); k-step s reads chunk (2s + h) ^ swizzle
+        const int frag_swz = swizzle_of_row(l32);
+        const int a_frag_base = (wn * WTN * 32 + l32) * kRowBytes;
+        const int b_frag_base = kXBase + (wm * WTM * 32 + l32) * kRowBytes;
+        // DMA lane geometry: lane -> (row within a 16-row group, stored chunk slot)
+        const int dma_r = lane / kChunksPerRow;
+        const int dma_cs = lane % kChunksPerRow;
 
         // ---- per-lane byte offsets of the DMA sources, relative to the tile's first row ----
         const char *w_tile = (const char *)p.W + (size_t)n0 * row_stride;
@@ -178,14 +244,14 @@ __global__ __launch_bounds__(kThreads) void tile_kernel(const TileParams p)
         unsigned offa[kDmaA], offb[kDmaB];
 #pragma unroll
         for (int j = 0; j < kDmaA; ++j) {
-            const int row = wave * (BN / 4) + j * kRowsPerDma + dma_r;
+            const int row = wave * (BN / kWaves) + j * kRowsPerDma + dma_r;
             const int c = dma_cs ^ swizzle_of_row(row);
             const int rr = (n0 + row < N) ? row : (N - 1 - n0);  // clamp to the last valid row
             offa[j] = (unsigned)rr * (unsigned)row_stride + c * 16;
         }
 #pragma unroll
         for (int j = 0; j < kDmaB; ++j) {
-            const int row = wave * (BM / 4) + j * kRowsPerDma + dma_r;
+            const int row = wave * (BM / kWaves) + j * kRowsPerDma + dma_r;
             const int c = dma_cs ^ swizzle_of_row(row);
             const int rr = (m0 + row < M) ? row : (M - 1 - m0);
             offb[j] = (unsigned)rr * (unsigned)row_stride + c * 16;
@@ -204,13 +270,13 @@ __global__ __launch_bounds__(kThreads) void tile_kernel(const TileParams p)
         auto dma_one = [&](int slab, int x) {
             const int stage = slab % kStages;
             if (x < kDmaA) {
-                char *sa = smem + stage * kStageBytes + wave * (BN / 4) * kRowBytes;
+                char *sa = smem + stage * kWStride + wave * (BN / kWaves) * kRowBytes;
                 __builtin_amdgcn_raw_ptr_buffer_load_lds(
                     w_rsrc, (__attribute__((address_space(3))) void *)(sa + x * 1024), 16,
                     offa[x < kDmaA ? x : 0], slab * kRowBytes, 0, 0);
             } else {
                 const int y = x - kDmaA;
-                char *sb = smem + stage * kStageBytes + kABytes + wave * (BM / 4) * kRowBytes;
+                char *sb = smem + kXBase + stage * kXStride + wave * (BM / kWaves) * kRowBytes;
                 __builtin_amdgcn_raw_ptr_buffer_load_lds(
                     x_rsrc, (__attribute__((address_space(3))) void *)(sb + y * 1024), 16,
                     offb[y >= 0 && y < kDmaB ? y : 0], slab * kRowBytes, 0, 0);
@@ -220,17 +286,16 @@ __global__ __launch_bounds__(kThreads) void tile_kernel(const TileParams p)
         auto issue_cut = [&](int slab, int half) {
             // lane geometry re-derived through an opaque move: this rarely taken path
             // must not have its masks precomputed (and spilled) at kernel entry
-            int lane_c;
-            asm volatile("v_mov_b32 %0, %1" : "=v"(lane_c) : "v"(lane));
+            const int lane_c = opaque_lane();
             const int dma_r = lane_c / kChunksPerRow;
             const int dma_cs = lane_c % kChunksPerRow;
             const int stage = slab % kStages;
             if (half == 0) {
-                char *sa = smem + stage * kStageBytes + wave * (BN / 4) * kRowBytes;
+                char *sa = smem + stage * kWStride + wave * (BN / kWaves) * kRowBytes;
                 const char *wk = w_tile + (size_t)slab * kRowBytes;
 #pragma unroll
                 for (int j = 0; j < kDmaA; ++j) {
-                    const int row = wave * (BN / 4) + j * kRowsPerDma + dma_r;
+                    const int row = wave * (BN / kWaves) + j * kRowsPerDma + dma_r;
                     const int c = dma_cs ^ swizzle_of_row(row);
                     const bool in = slab * kSlabElems + c * kChunkElems < K;
                     uintx4 v = *reinterpret_cast<const uintx4 *>(in ? wk + offa[j] : w_tile);
@@ -238,11 +303,11 @@ __global__ __launch_bounds__(kThreads) void tile_kernel(const TileParams p)
                     *reinterpret_cast<uintx4 *>(sa + j * 1024 + lane_c * 16) = v;
                 }
             } else {
-                char *sb = smem + stage * kStageBytes + kABytes + wave * (BM / 4) * kRowBytes;
+                char *sb = smem + kXBase + stage * kXStride + wave * (BM / kWaves) * kRowBytes;
                 const char *xk = x_tile + (size_t)slab * kRowBytes;
 #pragma unroll
                 for (int j = 0; j < kDmaB; ++j) {
-                    const int row = wave * (BM / 4) + j * kRowsPerDma + dma_r;
+                    const int row = wave * (BM / kWaves) + j * kRowsPerDma + dma_r;
                     const int c = dma_cs ^ swizzle_of_row(row);
                     const bool in = slab * kSlabElems + c * kChunkElems < K;
                     uintx4 v = *reinterpret_cast<const uintx4 *>(in ? xk + offb[j] : x_tile);
@@ -264,14 +329,13 @@ __global__ __launch_bounds__(kThreads) void tile_kernel(const TileParams p)
         uintx4 fa[2][WTN], fb[2][WTM];  // fragment registers, double-buffered by k-step
         // x-th fragment read of (slab, k-step s): W fragments first, then X fragments
         auto read_one = [&](int slab, int s, int x, uintx4 (&a)[WTN], uintx4 (&b)[WTM]) {
-            const char *sbase = smem + (slab % kStages) * kStageBytes;
             const int coff = ((2 * s + h) ^ frag_swz) << 4;
             if (x < WTN)
                 a[x < WTN ? x : 0] = *reinterpret_cast<const uintx4 *>(
-                    sbase + a_frag_base + x * 32 * kRowBytes + coff);
+                    smem + (slab % kStages) * kWStride + a_frag_base + x * 32 * kRowBytes + coff);
             else
                 b[x >= WTN ? x - WTN : 0] = *reinterpret_cast<const uintx4 *>(
-                    sbase + b_frag_base + (x - WTN) * 32 * kRowBytes + coff);
+                    smem + (slab % kStages) * kXStride + b_frag_base + (x - WTN) * 32 * kRowBytes + coff);
         };
         auto load_frags = [&](int slab, int s, uintx4 (&a)[WTN], uintx4 (&b)[WTM]) {
 #pragma unroll
@@ -312,7 +376,7 @@ __global__ __launch_bounds__(kThreads) void tile_kernel(const TileParams p)
         // k-step 3 is the point where slab i+1 has landed for everyone and everyone
         // has finished reading slab i (its stage is then refilled).
         static_assert(kStepsPerSlab == 4 && kStages == 2, "loop body written for 4 k-steps, 2 stages");
-        static_assert(kDmaA <= kGroups && kDmaB <= kGroups, "one DMA instruction per MFMA group at most");
+        static_assert(kXReg || (kDmaA <= kGroups && kDmaB <= kGroups), "one DMA instruction per MFMA group at most");
         auto dma_half_any = [&](int slab, int half) {
             // half 0: W rows (x in [0, kDmaA)), half 1: X rows; K-cut slabs go through registers
             if (!k_ragged || slab + 1 < slabs) {
@@ -323,6 +387,129 @@ __global__ __launch_bounds__(kThreads) void tile_kernel(const TileParams p)
                 issue_cut(slab, half);
             }
         };
+        if constexpr (kXReg) {
+        // ---- main loop, X slabs through registers ----
+        // Iteration i: the X slab i+1 is requested at the start (global -> registers); after the
+        // first three k-steps barrier A says everyone has read slab i from the LDS; then the X
+        // registers go to the single X buffer, the W slab i+2 is requested into the stage slab i
+        // occupied, half of the last k-step's MFMAs cover the LDS writes, barrier B publishes the X
+        // slab (every wave has waited for its own share of W slab i+1 before it), and the rest of the
+        // last k-step covers the first fragment reads of slab i+1.  The other workgroup on the compute
+        // unit fills the matrix pipe while this one stands at its barriers.
+        uintx4 xr[kDmaB];
+        auto x_load_full = [&](int slab) {
+#pragma unroll
+            for (int j = 0; j < kDmaB; ++j)
+                xr[j] = __builtin_bit_cast(uintx4, __builtin_amdgcn_raw_buffer_load_b128(
+                                                       x_rsrc, offb[j], slab * kRowBytes, 0));
+        };
+        auto x_load = [&](int slab) {
+            if (!k_ragged || slab + 1 < slabs) {
+                x_load_full(slab);
+            } else {
+                const int lane_c = opaque_lane();  // as in issue_cut
+#pragma unroll
+                for (int j = 0; j < kDmaB; ++j) {
+                    const int row = wave * (BM / kWaves) + j * kRowsPerDma + lane_c / kChunksPerRow;
+                    const int c = (lane_c % kChunksPerRow) ^ swizzle_of_row(row);
+                    const bool in = slab * kSlabElems + c * kChunkElems < K;
+                    uintx4 v = __builtin_bit_cast(uintx4, __builtin_amdgcn_raw_buffer_load_b128(
+                                                              x_rsrc, in ? offb[j] : 0u, in ? slab * kRowBytes : 0, 0));
+                    v &= in ? 0xffffffffu : 0u;
+                    xr[j] = v;
+                }
+            }
+        };
+        auto x_store = [&]() {
+            char *sb = smem + kXBase + wave * (BM / kWaves) * kRowBytes + lane * 16;
+#pragma unroll
+            for (int j = 0; j < kDmaB; ++j)
+                *reinterpret_cast<uintx4 *>(sb + j * 1024) = xr[j];
+        };
+        lds_barrier();  // the previous tile's epilogue is done with the LDS
+        dma_half_any(0, 0);
+        x_load(0);
+        if (slabs > 1)
+            dma_half_any(1, 0);
+        __builtin_amdgcn_s_waitcnt(0x0f70);  // vmcnt(0)
+        x_store();
+        lds_barrier();
+        stamp(1);
+        stamp(kTimelineCycleSlot);
+        load_frags(0, 0, fa[0], fb[0]);
+        // steady iterations: slab i+1 and slab i+2 exist and are full ones
+        const int n_steady = slabs - 2 - (k_ragged ? 1 : 0);
+        int i = 0;
+        for (; i < n_steady; ++i) {
+            x_load_full(i + 1);
+#pragma unroll
+            for (int g = 0; g < kGroups; ++g) {  // k-step 0
+                read_one(i, 1, g, fa[1], fb[1]);
+                mma_group(g, fa[0], fb[0]);
+                pin_group(g);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+#pragma unroll
+            for (int g = 0; g < kGroups; ++g) {  // k-step 1
+                mma_group(g, fa[1], fb[1]);
+                read_one(i, 2, g, fa[0], fb[0]);
+                pin_group(g);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+#pragma unroll
+            for (int g = 0; g < kGroups; ++g) {  // k-step 2
+                mma_group(g, fa[0], fb[0]);
+                read_one(i, 3, g, fa[1], fb[1]);
+                pin_group(g);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            lds_barrier();                       // A: everyone has read slab i
+            __builtin_amdgcn_s_waitcnt(0x0f70);  // vmcnt(0): X registers and this wave's W rows of slab i+1
+            x_store();
+#pragma unroll
+            for (int x = 0; x < kDmaA; ++x)
+                dma_one(i + 2, x);
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int g = 0; g < kGroups / 2; ++g) {  // k-step 3, first half
+                mma_group(g, fa[1], fb[1]);
+                pin_group(g);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+            lds_barrier();                       // B: slab i+1 is complete in the LDS
+            load_frags(i + 1, 0, fa[0], fb[0]);
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int g = kGroups / 2; g < kGroups; ++g) {  // k-step 3, second half
+                mma_group(g, fa[1], fb[1]);
+                pin_group(g);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        // last iterations: slab i+1 or i+2 is missing or cut by K
+        for (; i < slabs; ++i) {
+            const bool more = i + 1 < slabs;
+            if (more)
+                x_load(i + 1);
+            load_frags(i, 1, fa[1], fb[1]);
+            mma_all(fa[0], fb[0]);
+            load_frags(i, 2, fa[0], fb[0]);
+            mma_all(fa[1], fb[1]);
+            load_frags(i, 3, fa[1], fb[1]);
+            mma_all(fa[0], fb[0]);
+            if (more) {
+                lds_barrier();                       // A
+                __builtin_amdgcn_s_waitcnt(0x0f70);  // vmcnt(0)
+                x_store();
+                if (i + 2 < slabs)
+                    dma_half_any(i + 2, 0);
+                __builtin_amdgcn_s_waitcnt(0x0f70);  // a K-cut W slab went through registers
+                lds_barrier();                       // B
+                load_frags(i + 1, 0, fa[0], fb[0]);
+            }
+            mma_all(fa[1], fb[1]);
+        }
+        } else {
         // The previous tile's epilogue is done with the LDS once every wave is here (its LDS reads
         // completed before its stores could issue).  No wait for those stores: they drain while the
         // first slab of this tile travels.
@@ -331,13 +518,15 @@ __global__ __launch_bounds__(kThreads) void tile_kernel(const TileParams p)
         dma_half_any(0, 1);
         if (slabs > 1)
             dma_half_any(1, 0);
-        if (first_tile && slabs > 1 && !(k_ragged && slabs == 2))
+        if (first_tile && p.timeline == nullptr && slabs > 1 && !(k_ragged && slabs == 2))
             __builtin_amdgcn_s_waitcnt(0x0f70 | (kDmaA & 15) | ((kDmaA >> 4) << 14));  // slab 0 landed
         else
             __builtin_amdgcn_s_waitcnt(0x0f70);  // vmcnt(0): also the previous tile's stores, whose
                                                  // completion order relative to loads is not relied on
         first_tile = false;
         lds_barrier();
+        stamp(1);
+        stamp(kTimelineCycleSlot);
         load_frags(0, 0, fa[0], fb[0]);
 
         // steady iterations: slab i+1 and slab i+2 exist and are full ones
@@ -397,17 +586,18 @@ __global__ __launch_bounds__(kThreads) void tile_kernel(const TileParams p)
                 load_frags(i + 1, 0, fa[0], fb[0]);
             mma_all(fa[1], fb[1]);
         }
+        }  // kPipeDma
         __syncthreads();  // all fragment reads done: LDS becomes epilogue scratch
+        stamp(2);
+        stamp(kTimelineCycleSlot + 1);
 
         // ---- epilogue ----
-        // The thread index is re-read through an opaque move so that the epilogue's many
-        // lane-dependent addresses are computed here, once per tile, instead of being
-        // hoisted out of the tile loop and carried (spilled) across the main loop.
-        int tid_e;
-        asm volatile("v_mov_b32 %0, %1" : "=v"(tid_e) : "v"(threadIdx.x));
+        // The lane index and the row length are taken afresh so that the epilogue's many
+        // lane-dependent addresses and its float constants are computed here, once per tile,
+        // instead of being hoisted out of the tile loop and carried (spilled) across the main loop.
         {
-        const int tid = tid_e;
-        const int lane = tid & 63;
+        const int lane = opaque_lane();
+        const int M = opaque_uniform(p.M), N = opaque_uniform(p.N);
         const int h = lane >> 5;
         const int l32 = lane & 31;
         float *s_b = reinterpret_cast<float *>(smem + kOffPrm);
@@ -417,7 +607,7 @@ __global__ __launch_bounds__(kThreads) void tile_kernel(const TileParams p)
         floatx2 *s_rst = reinterpret_cast<floatx2 *>(smem + kOffRst);
         char *s_out = smem + kOffOut + wave * 32 * kOutPitch;
 
-        for (int c = tid; c < BN; c += kThreads) {
+        for (int c = wave * 64 + lane; c < BN; c += kThreads) {
             const int n = n0 + c;
             const bool ok = n < N;
             s_b[c] = (ok && p.b) ? load_as_float(reinterpret_cast<const T *>(p.b) + n) : 0.0f;
@@ -499,8 +689,8 @@ __global__ __launch_bounds__(kThreads) void tile_kernel(const TileParams p)
                     float m2_own = fmaxf(s2[j] - s1[j] * s1[j] * inv_own, 0.0f);
                     if (kRagged && cnt_own == 0)
                         mean_own = 0.0f;
-                    const float mean_oth = __shfl_xor(mean_own, 32);
-                    const float m2_oth = __shfl_xor(m2_own, 32);
+                    const float mean_oth = swap_halves(mean_own, lane);
+                    const float m2_oth = swap_halves(m2_own, lane);
                     float na = h == 0 ? n_own : n_oth;
                     float mean_a = h == 0 ? mean_own : mean_oth;
                     float m2a = h == 0 ? m2_own : m2_oth;
@@ -515,6 +705,7 @@ __global__ __launch_bounds__(kThreads) void tile_kernel(const TileParams p)
             (void)cntw_i;
         }
 
+        const int tid = wave * 64 + opaque_lane();  // taken afresh: not carried across the pass above
         if (MODE != kLinearOnly) {
             __syncthreads();
             if (tid < BM) {
@@ -537,6 +728,7 @@ __global__ __launch_bounds__(kThreads) void tile_kernel(const TileParams p)
             }
         }
 
+        stamp(3);
         if (MODE == kFused) {
             // exchange with the other tiles of these rows
             wait_published();
@@ -548,6 +740,7 @@ __global__ __launch_bounds__(kThreads) void tile_kernel(const TileParams p)
                     atomic_store_device(p.err, 1u);
             }
             __syncthreads();
+            stamp(4);
             if (tid < BM) {
                 // Plain loads: each line was written through by its single owner before
                 // the counter could reach its target, and no cache of this XCD can hold
@@ -576,6 +769,7 @@ __global__ __launch_bounds__(kThreads) void tile_kernel(const TileParams p)
             __syncthreads();
         }
 
+        stamp(5);
         // ---- (normalise,) convert, transpose through LDS, store 16-byte rows ----
         OutT *out_base = (MODE == kFused) ? reinterpret_cast<OutT *>(p.Y)
                                           : reinterpret_cast<OutT *>(p.F);
@@ -640,6 +834,7 @@ __global__ __launch_bounds__(kThreads) void tile_kernel(const TileParams p)
                 atomic_store_device(cnt + 1, 0u);
             }
         }
+        stamp(6);
         }  // epilogue scope
     }
 #else
@@ -700,38 +895,80 @@ __global__ __launch_bounds__(256) void finalize_kernel(const FinalizeParams p)
     }
 }
 
-template <typename T, int WT, int MODE>
+template <typename T, int WN, int WM, int WTN, int WTM, int MODE, int PIPE>
 hipError_t launch_tile(const TileParams &p, int grid, hipStream_t stream)
 {
-    constexpr int BN = kWavesN * WT * 32;
+    constexpr int BN = WN * WTN * 32;
+    constexpr int kThreads = 64 * WN * WM;
     if (p.N % BN != 0)
-        hipLaunchKernelGGL((tile_kernel<T, WT, WT, MODE, true>), dim3(grid), dim3(kThreads), 0, stream, p);
+        hipLaunchKernelGGL((tile_kernel<T, WN, WM, WTN, WTM, MODE, true, PIPE>), dim3(grid), dim3(kThreads), 0,
+                           stream, p);
     else
-        hipLaunchKernelGGL((tile_kernel<T, WT, WT, MODE, false>), dim3(grid), dim3(kThreads), 0, stream, p);
+        hipLaunchKernelGGL((tile_kernel<T, WN, WM, WTN, WTM, MODE, false, PIPE>), dim3(grid), dim3(kThreads), 0,
+                           stream, p);
     return hipGetLastError();
+}
+
+template <typename T, int WN, int WM, int WTN, int WTM, int MODE, int PIPE>
+int max_blocks_per_cu()
+{
+    int a = 0, b = 0;
+    constexpr int kThreads = 64 * WN * WM;
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&a, tile_kernel<T, WN, WM, WTN, WTM, MODE, true, PIPE>,
+                                                     kThreads, 0) != hipSuccess ||
+        hipOccupancyMaxActiveBlocksPerMultiprocessor(&b, tile_kernel<T, WN, WM, WTN, WTM, MODE, false, PIPE>,
+                                                     kThreads, 0) != hipSuccess) {
+        (void)hipGetLastError();
+        return 0;
+    }
+    return a < b ? a : b;
 }
 
 }  // namespace
 
-hipError_t launch_tile_kernel(bool bf16, int tile, int mode, const TileParams &p, int grid,
-                              hipStream_t stream)
+// Dispatch over (dtype, tile shape, mode): wave layout, blocks per wave and slab pipeline per shape.
+#define FF_TILE_DISPATCH(CALL)                                                             \
+    if (bf16) {                                                                            \
+        switch (shape) {                                                                   \
+        case kTile256x128: FF_MODES(__bf16, 2, 2, 4, 2, kPipeXReg, CALL)                   \
+        case kTile256W8: FF_MODES(__bf16, 2, 4, 4, 2, kPipeDma, CALL)                      \
+        case kTile256: FF_MODES(__bf16, 2, 2, 4, 4, kPipeDma, CALL)                        \
+        case kTile128: FF_MODES(__bf16, 2, 2, 2, 2, kPipeDma, CALL)                        \
+        default: FF_MODES(__bf16, 2, 2, 1, 1, kPipeDma, CALL)                              \
+        }                                                                                  \
+    }                                                                                      \
+    switch (shape) {                                                                       \
+    case kTile256x128: FF_MODES(float, 2, 2, 4, 2, kPipeXReg, CALL)                        \
+    case kTile256W8: FF_MODES(float, 2, 4, 4, 2, kPipeDma, CALL)                           \
+    case kTile256: FF_MODES(float, 2, 2, 4, 4, kPipeDma, CALL)                             \
+    case kTile128: FF_MODES(float, 2, 2, 2, 2, kPipeDma, CALL)                             \
+    default: FF_MODES(float, 2, 2, 1, 1, kPipeDma, CALL)                                   \
+    }
+#define FF_MODES(T, WN, WM, WTN, WTM, PIPE, CALL)                     \
+    switch (mode) {                                                   \
+    case kFused: return CALL(T, WN, WM, WTN, WTM, kFused, PIPE);      \
+    case kTwoPass: return CALL(T, WN, WM, WTN, WTM, kTwoPass, PIPE);  \
+    default: return CALL(T, WN, WM, WTN, WTM, kLinearOnly, PIPE);     \
+    }
+
+hipError_t launch_tile_kernel(bool bf16, int shape, int mode, const TileParams &p, int grid, hipStream_t stream)
 {
-#define FF_DISPATCH(T, WT)                                              \
-    switch (mode) {                                                     \
-    case kFused: return launch_tile<T, WT, kFused>(p, grid, stream);    \
-    case kTwoPass: return launch_tile<T, WT, kTwoPass>(p, grid, stream); \
-    default: return launch_tile<T, WT, kLinearOnly>(p, grid, stream);   \
-    }
-    if (bf16) {
-        if (tile == 256) { FF_DISPATCH(__bf16, 4) }
-        if (tile == 128) { FF_DISPATCH(__bf16, 2) }
-        FF_DISPATCH(__bf16, 1)
-    }
-    if (tile == 256) { FF_DISPATCH(float, 4) }
-    if (tile == 128) { FF_DISPATCH(float, 2) }
-    FF_DISPATCH(float, 1)
-#undef FF_DISPATCH
+#define FF_CALL(T, WN, WM, WTN, WTM, MODE, PIPE) launch_tile<T, WN, WM, WTN, WTM, MODE, PIPE>(p, grid, stream)
+    FF_TILE_DISPATCH(FF_CALL)
+#undef FF_CALL
 }
+
+// Workgroups of this kernel that fit one compute unit at once (registers, LDS), as the runtime
+// reports it; 0 if the query fails.  A launch whose workgroups wait for one another inside the
+// launch must not be larger than this many per compute unit.
+int tile_kernel_blocks_per_cu(bool bf16, int shape, int mode)
+{
+#define FF_CALL(T, WN, WM, WTN, WTM, MODE, PIPE) max_blocks_per_cu<T, WN, WM, WTN, WTM, MODE, PIPE>()
+    FF_TILE_DISPATCH(FF_CALL)
+#undef FF_CALL
+}
+#undef FF_MODES
+#undef FF_TILE_DISPATCH
 
 hipError_t launch_finalize_kernel(bool bf16, const FinalizeParams &p, hipStream_t stream)
 {

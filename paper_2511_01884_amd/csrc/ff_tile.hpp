@@ -7,6 +7,7 @@
 namespace ff {
 
 enum { kFused = 0, kTwoPass = 1, kLinearOnly = 2 };
+enum { kPipeDma = 0, kPipeXReg = 1 };
 
 struct TileParams {
     const void *X;       // [M,K]
@@ -24,10 +25,21 @@ struct TileParams {
     int NT;              // tiles along N
     int RB;              // row-blocks
     int rounds;          // ceil(RB * NT / grid)
-    int swz_sc;          // XCD-aware order: super-block width in tiles, 0 = plain order
+    int swz_sc_log2;     // XCD-aware order: log2 of the super-block width in tiles, -1 = plain order
+    int nt_log2;         // log2(NT) when the XCD-aware order is on
+    int grid_log2;       // log2(grid) when the XCD-aware order is on
+    long long stagger_ticks;  // start delay (wall-clock ticks) of the second half of the grid, 0 = none
     int extra_arrivals;  // test hook: added to the arrival target (non-zero makes waits expire)
     long long wait_ticks;
+    unsigned long long *timeline;  // test hook: phase timestamps, or null
+    int timeline_rounds;           // rounds of tiles the timeline buffer has room for
 };
+
+// Timeline record of one tile: slots 0..6 wall-clock stamps (tile start, first slab landed, main
+// loop done, statistics published, other tiles arrived, statistics merged, stores issued); slots
+// kTimelineCycleSlot, +1 the shader clock at the start and end of the main loop.
+constexpr int kTimelineSlots = 16;
+constexpr int kTimelineCycleSlot = 8;
 
 struct FinalizeParams {
     const float *G;
@@ -98,8 +110,22 @@ void metric_select_host(const double *r, const unsigned char *keep, int n, int J
 
 hipError_t launch_xent_kernel(bool bf16, const XentParams &p, hipStream_t stream);
 hipError_t launch_rowmean_chain(bool bf16, const RowMeanParams &p, hipStream_t stream);
-hipError_t launch_tile_kernel(bool bf16, int tile, int mode, const TileParams &p, int grid,
-                              hipStream_t stream);
+// Tile shapes of the tiled kernels (columns x rows of the output a workgroup owns).
+enum TileShape {
+    kTile64 = 0,       // 64 x 64, four wavefronts, up to four workgroups per compute unit
+    kTile128 = 1,      // 128 x 128, four wavefronts, two workgroups per compute unit
+    kTile256 = 2,      // 256 x 256, four wavefronts of 4 x 4 MFMA blocks, one workgroup per compute unit
+    kTile256W8 = 3,    // 256 x 256, eight wavefronts of 4 x 2 blocks, one workgroup per compute unit
+    kTile256x128 = 4,  // 256 columns x 128 rows, four wavefronts of 4 x 2 blocks, two workgroups per compute unit
+    kNumTileShapes = 5
+};
+inline int tile_shape_cols(int shape) { return shape == kTile64 ? 64 : (shape == kTile128 ? 128 : 256); }
+inline int tile_shape_rows(int shape)
+{
+    return shape == kTile64 ? 64 : ((shape == kTile128 || shape == kTile256x128) ? 128 : 256);
+}
+hipError_t launch_tile_kernel(bool bf16, int shape, int mode, const TileParams &p, int grid, hipStream_t stream);
+int tile_kernel_blocks_per_cu(bool bf16, int shape, int mode);
 hipError_t launch_finalize_kernel(bool bf16, const FinalizeParams &p, hipStream_t stream);
 hipError_t launch_smallm_kernel(int mt, const SmallMParams &p, int grid, hipStream_t stream);
 

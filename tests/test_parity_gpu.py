@@ -49,7 +49,7 @@ def test_full_matrix_parity(M, K, N, dtype, variant, expect):
     print(stats)
 
 
-@pytest.mark.parametrize("tile,per_cu", [(64, 1), (64, 2), (128, 1), (128, 2), (256, 1)])
+@pytest.mark.parametrize("tile,per_cu", [(64, 1), (64, 2), (128, 1), (128, 2), (256, 1), (256, 2)])
 @pytest.mark.parametrize("variant", [FUSED, TWOPASS])
 def test_forced_tile_shapes_parity(tile, per_cu, variant):
     """The tile shapes the automatic plan does not pick for this size are kernels of the same
@@ -64,7 +64,7 @@ def test_forced_tile_shapes_parity(tile, per_cu, variant):
     assert used == variant
     print(check_against_oracle(Y, oracle_on(d), "bf16", "tile %d x%d" % (tile, per_cu)))
     with pytest.raises(B.FFError):
-        B.ff_debug_force_tile(256, 2)
+        B.ff_debug_force_tile(256, 3)
     with pytest.raises(B.FFError):
         B.ff_debug_force_tile(32, 1)
 
