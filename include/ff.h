@@ -96,6 +96,29 @@ int ff_fused_linear_gelu_ln(const void *X, const void *W, const void *b,
                             void *Y, void *stream);
 
 /*
+ * The same operator for callers that cannot allocate device memory: code under HIP graph capture
+ * before any workspace exists, tight serving loops, harnesses that forbid hipMalloc.  Arguments,
+ * layout, dtypes, errors and result (bit for bit) as ff_fused_linear_gelu_ln, but no workspace is
+ * used, bound or allocated: the row statistics and arrival counters of the call live in a static
+ * device array inside the library (ff_noalloc_max_bytes() bytes, 8 MiB, one copy on every device
+ * that loads the library, held until the process ends).  The call makes no hipMalloc, hipFree,
+ * memset or synchronising call; it launches one small kernel that clears the counters it is about
+ * to use, then the operator's kernel, both on `stream`.  Shapes whose scratch need exceeds the array
+ * return FF_ERR_WORKSPACE: that is every shape ff_workspace_bytes() reports above the limit, in
+ * particular rows spanning more tiles than fit the device at once (the two-pass variant needs an fp32
+ * copy of G).  All calls on one device share the one array: calls that overlap in time on a device
+ * (two streams, two host threads) race on it and give wrong results; serialise them.
+ * ff_check_device() covers these calls too.
+ */
+int ff_fused_linear_gelu_ln_noalloc(const void *X, const void *W, const void *b,
+                                    const void *gamma, const void *beta, float eps,
+                                    int64_t M, int64_t K, int64_t N, int dtype,
+                                    void *Y, void *stream);
+
+/* Size of the static scratch array behind ff_fused_linear_gelu_ln_noalloc, in bytes. */
+size_t ff_noalloc_max_bytes(void);
+
+/*
  * Row-wise cross-entropy with mean reduction, the row reduction of the paper's case
  * study (Sec. 4: row maximum, sum of exponentials, pick of the target's logit):
  *     loss[r] = log( sum_c exp(L[r][c]) ) - L[r][t[r]],   *mean_loss = (1/B) sum_r loss[r]

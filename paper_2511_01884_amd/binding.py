@@ -17,7 +17,8 @@ FF_OK = 0
 FF_VARIANT_AUTO, FF_VARIANT_TILED_FUSED, FF_VARIANT_TILED_TWOPASS, FF_VARIANT_SMALL_M = 0, 1, 2, 3
 
 EXPORTS = [
-    "ff_fused_linear_gelu_ln", "ff_fused_linear_sub_rowmean_gelu_residual", "ff_rowmean_workspace_bytes",
+    "ff_fused_linear_gelu_ln", "ff_fused_linear_gelu_ln_noalloc", "ff_noalloc_max_bytes",
+    "ff_fused_linear_sub_rowmean_gelu_residual", "ff_rowmean_workspace_bytes",
     "ff_cross_entropy_mean", "ff_cross_entropy_workspace_bytes",
     "ff_metric_selection", "ff_metric_select_host",
     "ff_workspace_bytes", "ff_set_workspace", "ff_check_device",
@@ -46,6 +47,10 @@ def load() -> ctypes.CDLL:
         vp, i64, ci = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int
         lib.ff_fused_linear_gelu_ln.restype = ci
         lib.ff_fused_linear_gelu_ln.argtypes = [vp, vp, vp, vp, vp, ctypes.c_float, i64, i64, i64, ci, vp, vp]
+        lib.ff_fused_linear_gelu_ln_noalloc.restype = ci
+        lib.ff_fused_linear_gelu_ln_noalloc.argtypes = [vp, vp, vp, vp, vp, ctypes.c_float, i64, i64, i64, ci, vp, vp]
+        lib.ff_noalloc_max_bytes.restype = ctypes.c_size_t
+        lib.ff_noalloc_max_bytes.argtypes = []
         lib.ff_fused_linear_sub_rowmean_gelu_residual.restype = ci
         lib.ff_fused_linear_sub_rowmean_gelu_residual.argtypes = [vp, vp, vp, vp, i64, i64, i64, ci, vp, vp]
         lib.ff_rowmean_workspace_bytes.restype = ctypes.c_size_t
@@ -227,9 +232,21 @@ def ff_debug_expect_extra_arrivals(count: int) -> None:
         raise FFError(rc)
 
 
+def ff_noalloc_max_bytes() -> int:
+    return int(load().ff_noalloc_max_bytes())
+
+
+def ff_fused_linear_gelu_ln_noalloc(X: torch.Tensor, W: torch.Tensor, b: Optional[torch.Tensor],
+                                    gamma: Optional[torch.Tensor], beta: Optional[torch.Tensor],
+                                    eps: float, Y: torch.Tensor, stream=None) -> torch.Tensor:
+    """The entry point that allocates nothing: the caller passes every tensor, Y included."""
+    return ff_fused_linear_gelu_ln(X, W, b, gamma, beta, eps, Y=Y, stream=stream, _entry="ff_fused_linear_gelu_ln_noalloc")
+
+
 def ff_fused_linear_gelu_ln(X: torch.Tensor, W: torch.Tensor, b: Optional[torch.Tensor],
                             gamma: Optional[torch.Tensor], beta: Optional[torch.Tensor],
-                            eps: float, Y: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+                            eps: float, Y: Optional[torch.Tensor] = None, stream=None,
+                            _entry: str = "ff_fused_linear_gelu_ln") -> torch.Tensor:
     """Y = LayerNorm_N(GELU(X W^T + b)) * gamma + beta on the device of X.
     Allocates Y with torch if not given; everything else happens in libff.so."""
     if X.dim() != 2 or W.dim() != 2 or X.shape[1] != W.shape[1]:
@@ -244,9 +261,9 @@ def ff_fused_linear_gelu_ln(X: torch.Tensor, W: torch.Tensor, b: Optional[torch.
     elif tuple(Y.shape) != (M, N):
         raise ValueError("Y must be [M,N]")
     with torch.cuda.device(X.device):
-        rc = load().ff_fused_linear_gelu_ln(_ptr(X), _ptr(W, X), _ptr(b, X), _ptr(gamma, X),
-                                            _ptr(beta, X), float(eps), M, K, N, _dtype_code(X),
-                                            _ptr(Y, X), _stream(stream))
+        rc = getattr(load(), _entry)(_ptr(X), _ptr(W, X), _ptr(b, X), _ptr(gamma, X),
+                                     _ptr(beta, X), float(eps), M, K, N, _dtype_code(X),
+                                     _ptr(Y, X), _stream(stream))
     if rc != FF_OK:
         raise FFError(rc)
     return Y

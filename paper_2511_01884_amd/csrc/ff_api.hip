@@ -14,6 +14,21 @@ using namespace ff;
 
 constexpr int kMaxDevices = 64;
 
+// Scratch memory of the entry point that allocates nothing: error word, arrival counters and per-tile
+// row statistics of one call, laid out like a workspace.  One copy per device that loads the library,
+// held until the process ends.  Host code never uses this name as an address: the per-device address
+// comes from hipGetSymbolAddress (no_alloc_scratch below).
+constexpr size_t kNoAllocBytes = 8u << 20;
+static __device__ __align__(256) unsigned char scratch[kNoAllocBytes];
+
+// Clears the first `words` 32-bit words at `dst` (a fill kernel, not a memset node, so that a caller may
+// record it into a graph).
+__global__ __launch_bounds__(256) void clear_words_kernel(unsigned *dst, size_t words)
+{
+    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < words; i += (size_t)gridDim.x * 256)
+        dst[i] = 0u;
+}
+
 struct DeviceState {
     bool probed = false;
     int num_cus = 256;
@@ -21,6 +36,8 @@ struct DeviceState {
     void *ws = nullptr;       // bound or owned workspace; its control region is zeroed when it is bound or allocated
     size_t ws_bytes = 0;
     bool ws_owned = false;
+    void *no_alloc_ptr = nullptr;            // this device's copy of `scratch`, once asked for
+    bool no_alloc_used = false;
     unsigned long long *timeline = nullptr;  // test hook: phase timestamps of the tiled kernels
     size_t timeline_bytes = 0;
     signed char blocks_per_cu[2][kNumTileShapes][3] = {};  // cached occupancy answers [bf16][shape][mode], 0 = not asked
@@ -261,9 +278,24 @@ int prepare_workspace(DeviceState &st, size_t bytes, hipStream_t stream)
 
 bool misaligned(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) != 0; }
 
+// This device's copy of the static scratch array (asked of the runtime once per device, with that
+// device current), or null if the runtime refuses.
+void *no_alloc_scratch(DeviceState &st)
+{
+    if (st.no_alloc_ptr == nullptr) {
+        void *ptr = nullptr;
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || ptr == nullptr) {
+            (void)hipGetLastError();
+            return nullptr;
+        }
+        st.no_alloc_ptr = ptr;
+    }
+    return st.no_alloc_ptr;
+}
+
 int run(const void *X, const void *W, const void *b, const void *gamma, const void *beta, float eps,
         int64_t M, int64_t K, int64_t N, int dtype, void *Y, float *Z, bool linear_only,
-        hipStream_t stream)
+        hipStream_t stream, bool no_alloc = false)
 {
     int rc = validate_shape(M, K, N, dtype);
     if (rc != FF_OK)
@@ -282,11 +314,33 @@ int run(const void *X, const void *W, const void *b, const void *gamma, const vo
     rc = make_plan(M, K, N, dtype, st->num_cus, st, g_forced_variant, linear_only, pl);
     if (rc != FF_OK)
         return rc;
-    rc = prepare_workspace(*st, pl.total_bytes, stream);
-    if (rc != FF_OK)
-        return rc;
-
-    char *ws = static_cast<char *>(st->ws);
+    char *ws = nullptr;
+    if (no_alloc) {
+        // the static array is the workspace; what the kernels expect to find zero (error word, the
+        // arrival counters this plan uses) is cleared by a kernel on the caller's stream first
+        if (pl.total_bytes > kNoAllocBytes)
+            return FF_ERR_WORKSPACE;
+        ws = static_cast<char *>(no_alloc_scratch(*st));
+        if (ws == nullptr)
+            return FF_ERR_LAUNCH;
+        const size_t ctrl = pl.variant == FF_VARIANT_SMALL_M
+                                ? kCounterOffset + (size_t)kSyncWays * kSyncStride * sizeof(unsigned)
+                                : kCounterOffset + (size_t)pl.RB * 2 * sizeof(unsigned);
+        // the error word (offset 0) is cleared by the first call on a device only: later calls leave a
+        // failure flagged by an earlier one for ff_check_device to report
+        const size_t first = st->no_alloc_used ? kCounterOffset : 0;
+        const size_t words = (ctrl - first + 3) / 4;
+        hipLaunchKernelGGL(clear_words_kernel, dim3((unsigned)((words + 255) / 256 < 64 ? (words + 255) / 256 : 64)),
+                           dim3(256), 0, stream, reinterpret_cast<unsigned *>(ws + first), words);
+        if (hipGetLastError() != hipSuccess)
+            return FF_ERR_LAUNCH;
+        st->no_alloc_used = true;
+    } else {
+        rc = prepare_workspace(*st, pl.total_bytes, stream);
+        if (rc != FF_OK)
+            return rc;
+        ws = static_cast<char *>(st->ws);
+    }
     unsigned *err = reinterpret_cast<unsigned *>(ws);
     unsigned *counters = reinterpret_cast<unsigned *>(ws + kCounterOffset);
     const long long wait_ticks = g_wait_limit_us * st->ticks_per_us;
@@ -357,6 +411,16 @@ int ff_fused_linear_gelu_ln(const void *X, const void *W, const void *b, const v
     return run(X, W, b, gamma, beta, eps, M, K, N, dtype, Y, nullptr, false,
                static_cast<hipStream_t>(stream));
 }
+
+int ff_fused_linear_gelu_ln_noalloc(const void *X, const void *W, const void *b, const void *gamma,
+                                    const void *beta, float eps, int64_t M, int64_t K, int64_t N, int dtype,
+                                    void *Y, void *stream)
+{
+    return run(X, W, b, gamma, beta, eps, M, K, N, dtype, Y, nullptr, false,
+               static_cast<hipStream_t>(stream), true);
+}
+
+size_t ff_noalloc_max_bytes(void) { return kNoAllocBytes; }
 
 int ff_debug_linear(const void *X, const void *W, const void *b, int64_t M, int64_t K, int64_t N,
                     int dtype, float *Z_f32, void *stream)
@@ -653,18 +717,23 @@ int ff_check_device(void *stream)
         (void)hipGetLastError();
         return FF_ERR_LAUNCH;
     }
-    if (st->ws == nullptr)
-        return FF_OK;
-    unsigned flag = 0;
-    if (hipMemcpy(&flag, st->ws, sizeof(flag), hipMemcpyDeviceToHost) != hipSuccess) {
-        (void)hipGetLastError();
-        return FF_ERR_LAUNCH;
+    bool failed = false;
+    void *regions[2] = {st->ws, st->no_alloc_used ? st->no_alloc_ptr : nullptr};
+    for (void *region : regions) {
+        if (region == nullptr)
+            continue;
+        unsigned flag = 0;
+        if (hipMemcpy(&flag, region, sizeof(flag), hipMemcpyDeviceToHost) != hipSuccess) {
+            (void)hipGetLastError();
+            return FF_ERR_LAUNCH;
+        }
+        if (flag != 0) {
+            // a wait gave up: counters may be half-way; start from a clean control region
+            (void)hipMemset(region, 0, kCtrlBytes);
+            failed = true;
+        }
     }
-    if (flag == 0)
-        return FF_OK;
-    // a wait gave up: counters may be half-way; start from a clean control region
-    (void)hipMemset(st->ws, 0, kCtrlBytes);
-    return FF_ERR_DEVICE;
+    return failed ? FF_ERR_DEVICE : FF_OK;
 }
 
 const char *ff_status_string(int status)
