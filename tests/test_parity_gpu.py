@@ -160,10 +160,11 @@ def test_rows_wider_than_the_grid_take_the_two_pass_path_by_themselves():
     assert e.value.status == 5
 
 
-@pytest.mark.parametrize("name", ["cfg1", "cfg2"])
+@pytest.mark.parametrize("name", ["cfg1", "cfg2", "cfg4"])
 def test_benchmark_sizes_full_matrix(name):
-    """Every element of the two benchmark shapes the oracle finishes in seconds on the host's threads,
-    in the launch configuration the benchmark times; a second run must give the same bits."""
+    """Every element of the three large benchmark shapes (the oracle takes seconds to tens of seconds on
+    the host's threads), in the launch configuration the benchmark times; a second run must give the
+    same bits."""
     wl = CONFIGS[name]
     _announce("full matrix", name)
     d = make_inputs(wl.M, wl.K, wl.N, wl.dtype, seed=0)
@@ -334,6 +335,94 @@ def test_graph_replay_matches_eager(M, K, N):
     B.ff_check_device()
     ref_in = dict(d, X=dev["X"].cpu(), W=dev["W"].cpu())
     check_against_oracle(Y_static, oracle_on(ref_in), "bf16")
+
+
+def test_first_call_on_a_fresh_workspace_can_be_captured():
+    """The first call after binding a caller-owned workspace (full of NaN patterns) is recorded into a
+    graph without any eager call before it: binding cleared the control region itself, the call issues
+    nothing but its kernel.  Every replay must equal the oracle's result."""
+    M, K, N = 1300, 264, 2056
+    d = make_inputs(M, K, N, "bf16", seed=24)
+    dev = {k: (v.cuda() if isinstance(v, torch.Tensor) else v) for k, v in d.items()}
+    need = B.ff_workspace_bytes(M, K, N, B.FF_BF16)
+    ws = torch.full((need // 4 + 64,), float("nan"), dtype=torch.float32, device="cuda")
+    Y = torch.zeros((M, N), dtype=torch.bfloat16, device="cuda")
+    torch.cuda.synchronize()
+    B.ff_set_workspace(ws)
+    try:
+        g = torch.cuda.CUDAGraph()
+        s = torch.cuda.Stream()
+        with torch.cuda.stream(s):
+            with torch.cuda.graph(g, stream=s):
+                B.ff_fused_linear_gelu_ln(dev["X"], dev["W"], dev["b"], dev["gamma"], dev["beta"], d["eps"], Y=Y)
+        torch.cuda.synchronize()
+        ref = oracle_on(d)
+        for rep in range(3):
+            Y.zero_()
+            torch.cuda.synchronize()
+            g.replay()
+            torch.cuda.synchronize()
+            check_against_oracle(Y, ref, "bf16", "captured first call, replay %d" % rep)
+        B.ff_check_device()
+    finally:
+        B.ff_set_workspace(None)
+
+
+def test_growing_the_own_workspace_during_capture_is_refused():
+    """With no caller workspace bound, a call that needs more scratch than the library holds cannot
+    allocate while its stream is being captured: it must say so (FF_ERR_WORKSPACE) and leave the
+    capture valid; outside the capture the same call allocates and works."""
+    M, K, N = 4100, 64, 8200          # forced two-pass: fp32 G of 134 MB, larger than any earlier need
+    d = make_inputs(M, K, N, "bf16", seed=25)
+    dev = {k: (v.cuda() if isinstance(v, torch.Tensor) else v) for k, v in d.items()}
+    small = make_inputs(64, 64, 64, "bf16", seed=25)
+    sdev = {k: (v.cuda() if isinstance(v, torch.Tensor) else v) for k, v in small.items()}
+    Y = torch.empty((M, N), dtype=torch.bfloat16, device="cuda")
+    Ys = torch.empty((64, 64), dtype=torch.bfloat16, device="cuda")
+    B.ff_set_workspace(ws := torch.zeros(1 << 18, dtype=torch.float32, device="cuda"))  # drop a large own one
+    B.ff_set_workspace(None)
+    del ws
+    B.ff_fused_linear_gelu_ln(sdev["X"], sdev["W"], sdev["b"], sdev["gamma"], sdev["beta"], small["eps"], Y=Ys)
+    torch.cuda.synchronize()
+    B.ff_debug_force_variant(TWOPASS)
+    status = None
+    try:
+        g = torch.cuda.CUDAGraph()
+        s = torch.cuda.Stream()
+        with torch.cuda.stream(s):
+            with torch.cuda.graph(g, stream=s):
+                try:
+                    B.ff_fused_linear_gelu_ln(dev["X"], dev["W"], dev["b"], dev["gamma"], dev["beta"], d["eps"], Y=Y)
+                except B.FFError as e:
+                    status = e.status
+                B.ff_debug_force_variant(AUTO)
+                B.ff_fused_linear_gelu_ln(sdev["X"], sdev["W"], sdev["b"], sdev["gamma"], sdev["beta"],
+                                          small["eps"], Y=Ys)
+        torch.cuda.synchronize()
+        assert status == 6
+        Ys.zero_()
+        g.replay()                       # the capture survived the refused call
+        torch.cuda.synchronize()
+        check_against_oracle(Ys, oracle_on(small), "bf16", "small call captured after the refusal")
+        Y2, used = gpu_run(d, TWOPASS)   # eager: allocates and works
+        assert used == TWOPASS
+        rows = sample_rows(M, 24)
+        check_against_oracle(Y2[torch.tensor(rows)], oracle_on(d, rows=rows), "bf16", "two-pass after growing")
+    finally:
+        B.ff_debug_force_variant(AUTO)
+
+
+def test_two_workgroups_per_compute_unit_wait_for_each_other():
+    """A shape for which the automatic plan takes 128-tiles with more workgroups than compute units
+    (two per unit, all of which must be resident because they wait for one another inside the launch)."""
+    M, K, N = 1024, 256, 8192
+    _announce("two per unit", M, K, N)
+    d = make_inputs(M, K, N, "bf16", seed=26)
+    Y, used = gpu_run(d, AUTO)
+    assert used == FUSED
+    print(check_against_oracle(Y, oracle_on(d), "bf16", "1024x256x8192"))
+    Y2, _ = gpu_run(d, AUTO)
+    assert torch.equal(Y, Y2)
 
 
 def test_workspace_grows_between_shapes():
