@@ -21,12 +21,21 @@ constexpr int kMaxDevices = 64;
 constexpr size_t kNoAllocBytes = 8u << 20;
 static __device__ __align__(256) unsigned char scratch[kNoAllocBytes];
 
-// Clears the first `words` 32-bit words at `dst` (a fill kernel, not a memset node, so that a caller may
-// record it into a graph).
-__global__ __launch_bounds__(256) void clear_words_kernel(unsigned *dst, size_t words)
+// Sets `words` 32-bit words at `dst` to `value` (a fill kernel, not a memset node, so that a caller
+// may record it into a graph).
+__global__ __launch_bounds__(256) void fill_words_kernel(unsigned *dst, size_t words, unsigned value)
 {
     for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < words; i += (size_t)gridDim.x * 256)
-        dst[i] = 0u;
+        dst[i] = value;
+}
+
+// The state a workspace must be in between launches: error word and counters zero.
+hipError_t init_control_region(void *ws)
+{
+    hipError_t e = hipMemset(ws, 0, kCtrlBytes);
+    if (e == hipSuccess)
+        e = hipDeviceSynchronize();
+    return e;
 }
 
 struct DeviceState {
@@ -265,7 +274,7 @@ int prepare_workspace(DeviceState &st, size_t bytes, hipStream_t stream)
         (void)hipGetLastError();
         return FF_ERR_WORKSPACE;
     }
-    if (hipMemset(mem, 0, kCtrlBytes) != hipSuccess || hipDeviceSynchronize() != hipSuccess) {
+    if (init_control_region(mem) != hipSuccess) {
         (void)hipGetLastError();
         (void)hipFree(mem);
         return FF_ERR_LAUNCH;
@@ -323,15 +332,15 @@ int run(const void *X, const void *W, const void *b, const void *gamma, const vo
         ws = static_cast<char *>(no_alloc_scratch(*st));
         if (ws == nullptr)
             return FF_ERR_LAUNCH;
-        const size_t ctrl = pl.variant == FF_VARIANT_SMALL_M
-                                ? kCounterOffset + (size_t)kSyncWays * kSyncStride * sizeof(unsigned)
-                                : kCounterOffset + (size_t)pl.RB * 2 * sizeof(unsigned);
         // the error word (offset 0) is cleared by the first call on a device only: later calls leave a
         // failure flagged by an earlier one for ff_check_device to report
         const size_t first = st->no_alloc_used ? kCounterOffset : 0;
+        const size_t ctrl = pl.variant == FF_VARIANT_SMALL_M
+                                ? kCounterOffset + (size_t)kSyncWays * kSyncStride * sizeof(unsigned)
+                                : kCounterOffset + (size_t)pl.RB * 2 * sizeof(unsigned);
         const size_t words = (ctrl - first + 3) / 4;
-        hipLaunchKernelGGL(clear_words_kernel, dim3((unsigned)((words + 255) / 256 < 64 ? (words + 255) / 256 : 64)),
-                           dim3(256), 0, stream, reinterpret_cast<unsigned *>(ws + first), words);
+        hipLaunchKernelGGL(fill_words_kernel, dim3((unsigned)((words + 255) / 256 < 64 ? (words + 255) / 256 : 64)),
+                           dim3(256), 0, stream, reinterpret_cast<unsigned *>(ws + first), words, 0u);
         if (hipGetLastError() != hipSuccess)
             return FF_ERR_LAUNCH;
         st->no_alloc_used = true;
@@ -357,6 +366,10 @@ int run(const void *X, const void *W, const void *b, const void *gamma, const vo
         p.strips = pl.strips;
         p.extra_arrivals = g_extra_arrivals;
         p.wait_ticks = wait_ticks;
+        p.timeline = (st->timeline != nullptr &&
+                      st->timeline_bytes >= (size_t)pl.grid * kTimelineSlots * sizeof(unsigned long long))
+                         ? st->timeline
+                         : nullptr;
         if (launch_smallm_kernel(pl.mt, p, pl.grid, stream) != hipSuccess)
             return FF_ERR_LAUNCH;
         t_last_variant = pl.variant;
@@ -690,8 +703,7 @@ int ff_set_workspace(void *dev_ptr, size_t bytes)
         return FF_ERR_ALIGN;
     if (dev_ptr != nullptr && bytes < kCtrlBytes)
         return FF_ERR_WORKSPACE;
-    if (dev_ptr != nullptr &&
-        (hipMemset(dev_ptr, 0, kCtrlBytes) != hipSuccess || hipDeviceSynchronize() != hipSuccess)) {
+    if (dev_ptr != nullptr && init_control_region(dev_ptr) != hipSuccess) {
         (void)hipGetLastError();
         return FF_ERR_LAUNCH;  // the old binding stays
     }
@@ -729,7 +741,7 @@ int ff_check_device(void *stream)
         }
         if (flag != 0) {
             // a wait gave up: counters may be half-way; start from a clean control region
-            (void)hipMemset(region, 0, kCtrlBytes);
+            (void)init_control_region(region);
             failed = true;
         }
     }

@@ -17,13 +17,24 @@ typedef unsigned int uintx4 __attribute__((ext_vector_type(4)));
 typedef unsigned int uintx2 __attribute__((ext_vector_type(2)));
 
 // ---- workspace layout (bytes from the workspace base) ----------------------
-// [0, 4)                error word: non-zero once a cross-tile wait gave up
-// [256, CTRL_BYTES)     arrival / departure counters, two uint32 per row-block
+// [0, 4)                error word: non-zero once a wait inside a launch gave up
+// [256, CTRL_BYTES)     arrival / departure counters, two uint32 per row-block; zero between launches
 // [CTRL_BYTES, ...)     per-tile row statistics (float2 mean, M2), then the
-//                       two-pass variant's fp32 G
+//                       two-pass variant's fp32 G; other entry points' scratch
 constexpr size_t kCtrlBytes = 1u << 20;
 constexpr size_t kCounterOffset = 256;
 constexpr int64_t kMaxRowBlocks = (int64_t)((kCtrlBytes - kCounterOffset) / 8);
+
+// Workgroup barrier that carries no fence: unlike __syncthreads() it does not wait for outstanding
+// global loads, so loads requested ahead (registers or direct-to-LDS) stay in flight across it;
+// their completion is awaited explicitly with vmcnt where it matters.  It waits for this wave's own
+// LDS reads and writes, and the barrier instruction itself is a compiler-level ordering point for
+// memory operations.
+__device__ __forceinline__ void lds_barrier()
+{
+    __builtin_amdgcn_s_waitcnt(0xc07f);  // lgkmcnt(0) only
+    __builtin_amdgcn_s_barrier();
+}
 
 // ---- bf16 <-> fp32 -----------------------------------------------------------
 __device__ __forceinline__ float bf16_bits_to_float(unsigned short h)

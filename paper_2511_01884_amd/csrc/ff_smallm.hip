@@ -88,6 +88,16 @@ __global__ __launch_bounds__(kThreads) void smallm_kernel(const SmallMParams p)
         xrow[mt] = X + (size_t)(m < M ? m : M - 1) * K + x_kg * 8;
     }
 
+    // Phase timestamps (test hook): thread 0 writes the wall clock at the phase boundaries into
+    // timeline[workgroup * kTimelineSlots + k]: 0 start, 1 the first wavefront has streamed its share
+    // of K (last strip), 2 all have, 3 statistics published, 4 every workgroup has arrived, 5 statistics
+    // merged, 6 stores issued.
+    auto stamp = [&](int k) {
+        if (p.timeline != nullptr && tid == 0)
+            p.timeline[(size_t)blockIdx.x * kTimelineSlots + k] = wall_clock64();
+    };
+    stamp(0);
+
     int owned = 0;
     for (int strip = blockIdx.x; strip < p.strips; strip += gridDim.x, ++owned) {
         const int n0 = strip * kSmallMStripCols;
@@ -192,7 +202,9 @@ __global__ __launch_bounds__(kThreads) void smallm_kernel(const SmallMParams p)
         }
 
         // ---- sum the 8 waves' partial products in wave order ----
+        stamp(1);
         __syncthreads();  // s_part / s_g of the previous strip are no longer read
+        stamp(2);
         // Result layout of a 16x16 MFMA: lane (j = lane & 15, g = lane >> 4), register t
         // holds result row 4 g + t, column j.  Rows 0..7 of the lower-k accumulator and
         // rows 8..15 of the upper-k accumulator are the wanted products of W row
@@ -248,6 +260,7 @@ __global__ __launch_bounds__(kThreads) void smallm_kernel(const SmallMParams p)
     }
 
     // ---- exchange the strip statistics across the whole grid ----
+    stamp(3);
     wait_published();
     __syncthreads();
     const int way = blockIdx.x % kSyncWays;
@@ -261,6 +274,7 @@ __global__ __launch_bounds__(kThreads) void smallm_kernel(const SmallMParams p)
             atomic_store_device(p.err, 1u);
     }
     __syncthreads();
+    stamp(4);
     {
         // Every workgroup merges all strips' partials itself, in strip order: thread ->
         // (row, chunk of consecutive strips); chunks of a wave are then folded with
@@ -328,6 +342,7 @@ __global__ __launch_bounds__(kThreads) void smallm_kernel(const SmallMParams p)
         }
         __syncthreads();
     }
+    stamp(5);
     // ---- normalise and store ----
     owned = 0;
     for (int strip = blockIdx.x; strip < p.strips; strip += gridDim.x, ++owned) {
@@ -359,6 +374,7 @@ __global__ __launch_bounds__(kThreads) void smallm_kernel(const SmallMParams p)
         }
     }
 
+    stamp(6);
     // ---- departure: the last workgroup of the last way re-arms every counter ----
     // (only then has every workgroup left its wait, so no poller can see a counter go back to zero)
     if (tid == 0) {

@@ -67,17 +67,6 @@ __device__ __forceinline__ void wave_lds_sync()
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
-// Workgroup barrier for the K loop.  Unlike __syncthreads() it carries no fence,
-// so it does not wait for outstanding global loads: direct-to-LDS loads of later
-// slabs stay in flight across it (their completion is awaited explicitly with
-// vmcnt).  It waits for this wave's own LDS reads and writes, and the barrier
-// instruction itself is a compiler-level ordering point for memory operations.
-__device__ __forceinline__ void lds_barrier()
-{
-    __builtin_amdgcn_s_waitcnt(0xc07f);  // lgkmcnt(0) only
-    __builtin_amdgcn_s_barrier();
-}
-
 // Ordering point for the instruction scheduler: the listed accumulators must have
 // been produced before it, and no memory operation moves across it.
 __device__ __forceinline__ void pin_order(floatx16 &c0) { asm volatile("" : "+a"(c0) : : "memory"); }

@@ -62,6 +62,7 @@ struct SmallMParams {
     int strips;          // N / 32 rounded up
     int extra_arrivals;  // test hook: added to the arrival target (non-zero makes waits expire)
     long long wait_ticks;
+    unsigned long long *timeline;  // test hook: phase timestamps, or null
 };
 
 // second chain: 512 threads; phase 1 covers 64 rows x 128 bytes of W per load instruction
