@@ -136,10 +136,12 @@ int make_plan(int64_t M, int64_t K, int64_t N, int dtype, int num_cus, DeviceSta
         return FF_OK;
     }
 
-    // Tiled variants.  Large problems take 256 x 256 tiles, one workgroup per compute unit: eight
-    // wavefronts when the problem is a single round of tiles (their stores drain faster), four when
-    // a workgroup walks several tiles (measured: 4096^3 114.6 against 116.6 us; 65536 x 1024 x 1024
-    // 167.6 against 165.2 us; 8192 x 4096 x 16384 994 against 969 us).  Problems of at most half the
+    // Tiled variants.  Large problems take 256 x 256 tiles, one workgroup of eight wavefronts per
+    // compute unit.  Eight wavefronts run the epilogue faster than four (two wavefronts per SIMD hide
+    // each other's latencies: bias, GELU and statistics 7.6 against 9.4 us per tile, stores 4.1 against
+    // 6.3 us) and the K loop up to 4 % slower (half again as many LDS fragment reads per MFMA); the
+    // sum favours eight (one device, us: 4096^3 115.7 against 116.7; 65536 x 1024 x 1024 159.5 against
+    // 170.7; 8192 x 4096 x 16384 950 against 966).  Problems of at most half the
     // compute units' worth of 256-tiles take 128-tiles, two per compute unit, which finish in one
     // round; at most a quarter of the compute units' worth of 128-tiles: 64-tiles, which spread them
     // further.  The 256-column x 128-row tile, two workgroups per compute unit, is never chosen: the
@@ -147,8 +149,7 @@ int make_plan(int64_t M, int64_t K, int64_t N, int dtype, int num_cus, DeviceSta
     // L2 -> LDS traffic per flop (4096^3: 148 us).
     const int64_t tiles256 = ((M + 255) / 256) * ((N + 255) / 256);
     const int64_t tiles128 = ((M + 127) / 128) * ((N + 127) / 128);
-    pl.shape = tiles256 * 2 > num_cus ? (tiles256 <= num_cus ? kTile256W8 : kTile256)
-                                      : (tiles128 * 4 > num_cus ? kTile128 : kTile64);
+    pl.shape = tiles256 * 2 > num_cus ? kTile256W8 : (tiles128 * 4 > num_cus ? kTile128 : kTile64);
     if (g_forced_tile != 0) {
         pl.shape = g_forced_tile == 64 ? kTile64 : (g_forced_tile == 128 ? kTile128 : kTile256);
         if (g_forced_tile == 256 && g_forced_wg_per_cu == 2)

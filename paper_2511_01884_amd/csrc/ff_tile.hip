@@ -306,6 +306,10 @@ void tile_kernel(const TileParams p)
             }
         };
 
+        // The accumulators start from a zero the optimiser cannot see through: given a constant it
+        // parks a block of sixteen zeros in scratch memory for the path that skips the steady iterations.
+        float zero;
+        asm volatile("v_mov_b32 %0, 0" : "=v"(zero));
         floatx16 acc[WTN][WTM];
 #pragma unroll
         for (int i = 0; i < WTN; ++i)
@@ -313,7 +317,7 @@ void tile_kernel(const TileParams p)
             for (int j = 0; j < WTM; ++j)
 #pragma unroll
                 for (int r = 0; r < 16; ++r)
-                    acc[i][j][r] = 0.0f;
+                    acc[i][j][r] = zero;
 
         uintx4 fa[2][WTN], fb[2][WTM];  // fragment registers, double-buffered by k-step
         // x-th fragment read of (slab, k-step s): W fragments first, then X fragments
@@ -669,6 +673,11 @@ void tile_kernel(const TileParams p)
                 }
             }
             if (MODE != kLinearOnly) {
+                // (the lane index is taken afresh after the pass over the accumulators and again
+                // before the stores: values derived from it are not carried across those passes)
+                const int lane = opaque_lane();
+                const int h = lane >> 5;
+                const int l32 = lane & 31;
 #pragma unroll
                 for (int j = 0; j < WTM; ++j) {
                     // lane statistics -> merged with the other half-wave (lower half first)
@@ -762,6 +771,11 @@ void tile_kernel(const TileParams p)
         // ---- (normalise,) convert, transpose through LDS, store 16-byte rows ----
         OutT *out_base = (MODE == kFused) ? reinterpret_cast<OutT *>(p.Y)
                                           : reinterpret_cast<OutT *>(p.F);
+        const int lane_o = opaque_lane();
+        {
+        const int lane = lane_o;
+        const int h = lane >> 5;
+        const int l32 = lane & 31;
 #pragma unroll
         for (int j = 0; j < WTM; ++j) {
             float rstd = 1.0f, shift = 0.0f;  // y = (g * rstd + shift) * gamma + beta
@@ -808,10 +822,11 @@ void tile_kernel(const TileParams p)
                 const uintx4 v = *reinterpret_cast<const uintx4 *>(s_out + r * kOutPitch + c * 16);
                 const int gm = m0 + wm * WTM * 32 + j * 32 + r;
                 const int gn = n0 + ncol_wave + c * kChunkOut;
-                if (gm < M && gn < N)
-                    *reinterpret_cast<uintx4 *>(out_base + (size_t)gm * N + gn) = v;
+                if (gm < M && gn < N)  // streaming store: Y is not read again by this launch
+                    __builtin_nontemporal_store(v, reinterpret_cast<uintx4 *>(out_base + (size_t)gm * N + gn));
             }
             wave_lds_sync();
+        }
         }
         if (MODE == kFused && tid == 0) {
             // Departure, after the stores have been issued so that the wait for the counter's old value
