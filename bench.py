@@ -103,6 +103,60 @@ def batch_median_ms(torch, step, launches: int = 100, batches: int = 5) -> float
     return sorted(out)[len(out) // 2]
 
 
+def preheat(torch, step, ms: float) -> int:
+    """Untimed launches of the step for about `ms` of wall time, ahead of the warm-up steps: the chip leaves
+    its idle clock state only after some tens of milliseconds of load, far more than five warm-up launches."""
+    n = 0
+    t_end = time.perf_counter() + ms * 1e-3
+    while time.perf_counter() < t_end:
+        for _ in range(20):
+            step(n)
+            n += 1
+        torch.cuda.synchronize()
+    return n
+
+
+TILE_STAMPS = ["tile start", "first K slab in LDS", "K loop done", "GELU done, row statistics published",
+               "other tiles of the rows arrived", "statistics merged", "stores issued"]
+SMALLM_STAMPS = ["workgroup start", "first wavefront's K slice done", "all wavefronts done", "row statistics published",
+                 "other workgroups arrived", "statistics merged", "stores issued"]
+
+
+def phase_timeline(torch, B, step, small_m: bool, launches: int = 3):
+    """Per-phase durations of one launch from the kernels' own timestamps (ff_debug_set_timeline): the mean,
+    minimum and maximum over the workgroups' tiles of the last of `launches` launches."""
+    slots, max_tiles = 16, 16 * 512
+    buf = torch.zeros(max_tiles * slots, dtype=torch.int64, device="cuda")
+    B.ff_debug_set_timeline(buf)
+    try:
+        for i in range(launches):
+            step(i)
+        torch.cuda.synchronize()
+    finally:
+        B.ff_debug_set_timeline(None)
+    B.ff_check_device()
+    rec = buf.cpu().double().view(-1, slots)
+    rec = rec[rec[:, 0] > 0]
+    if len(rec) == 0:
+        return None
+    names = SMALLM_STAMPS if small_m else TILE_STAMPS
+    rel = (rec[:, :7] - rec[:, 0].min()) / 100.0          # 100 MHz wall clock -> microseconds
+    dur = rel[:, 1:] - rel[:, :-1]
+    out = {"tiles": int(len(rec)), "last_stamp_us": float(rel[:, 6].max()), "phases": []}
+    if not small_m:
+        mhz = (rec[:, 9] - rec[:, 8]) / ((rec[:, 2] - rec[:, 1]) / 100.0)
+        out["k_loop_shader_clock_mhz"] = float(mhz.mean())
+    for k in range(6):
+        out["phases"].append({"from": names[k], "to": names[k + 1], "mean_us": float(dur[:, k].mean()),
+                              "min_us": float(dur[:, k].min()), "max_us": float(dur[:, k].max())})
+    print("phase timeline (%d tiles, last stamp %.1f us after the first):" % (out["tiles"], out["last_stamp_us"]),
+          file=sys.stderr)
+    for ph in out["phases"]:
+        print("  %-38s -> %-38s mean %6.1f  min %6.1f  max %6.1f us" %
+              (ph["from"], ph["to"], ph["mean_us"], ph["min_us"], ph["max_us"]), file=sys.stderr)
+    return out
+
+
 def algorithmic_bytes(M, K, N, esize):
     """Each of X, W, b, gamma, beta read once and Y written once."""
     return (M * K + N * K + M * N + 3 * N) * esize
@@ -125,6 +179,11 @@ def main() -> int:
     ap.add_argument("--cache-warm", action="store_true",
                     help="also time launches on a single buffer set (not in the default run, so that every "
                          "launch of the default command has the rotating-buffer duration)")
+    ap.add_argument("--preheat-ms", type=float, default=300.0,
+                    help="untimed launches of the step for this long before the warm-up steps (0: none)")
+    ap.add_argument("--timeline", action="store_true",
+                    help="after the timed region, run three launches with the kernels' phase timestamps switched on "
+                         "and report the per-phase durations (cfg0..cfg4 and f32_4096 only)")
     ap.add_argument("--print-source-hash", action="store_true", help="print the kernel source hash and exit")
     args = ap.parse_args()
     if args.print_source_hash:
@@ -176,6 +235,7 @@ def main() -> int:
         X, W, Y = sets[i % n_sets]
         B.ff_fused_linear_gelu_ln(X, W, b, gamma, beta, eps, Y=Y)
 
+    n_pre = preheat(torch, step, args.preheat_ms)
     for i in range(args.warmup):
         step(i)
     B.ff_check_device()
@@ -224,14 +284,16 @@ def main() -> int:
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "bf16" if wl.dtype == "bf16" else "f32", "data": "synthetic",
         "config": {"workload": "%s: %s fused linear+GELU+LayerNorm M=%d K=%d N=%d" % (wl.name, wl.dtype, M, K, N),
-                   "variant": variant, "buffer_sets": n_sets,
+                   "variant": variant, "buffer_sets": n_sets, "preheat_launches": n_pre,
                    "gflop_per_step": flops / 1e9, "algorithmic_mb_per_step": abytes / 1e6},
         "roofline": roof,
     }
 
+    if args.timeline:
+        out["timeline"] = phase_timeline(torch, B, step, small_m=(variant == B.FF_VARIANT_SMALL_M))
+
     if not args.no_eager:
         import torch.nn.functional as F
-        X, W, _ = sets[0]
 
         def eager(i):
             X, W, _ = sets[i % n_sets]
@@ -296,6 +358,7 @@ def bench_rowmean(args, torch, B) -> int:
         X, W, Out = sets[i % n_sets]
         B.ff_fused_linear_sub_rowmean_gelu_residual(X, W, b, sv, Out=Out)
 
+    preheat(torch, step, args.preheat_ms)
     for i in range(args.warmup):
         step(i)
     torch.cuda.synchronize()
@@ -399,6 +462,7 @@ def bench_xent(args, torch, B) -> int:
         L, t, out = sets[i % n_sets]
         B.ff_cross_entropy_mean(L, t, mean_loss=out)
 
+    preheat(torch, step, args.preheat_ms)
     for i in range(args.warmup):
         step(i)
     torch.cuda.synchronize()

@@ -192,6 +192,17 @@ size_t ff_rowmean_workspace_bytes(int64_t M, int64_t K, int64_t N, int dtype);
 size_t ff_workspace_bytes(int64_t M, int64_t K, int64_t N, int dtype);
 
 /*
+ * The launch plan a call with this shape would take under the current variant selection, without
+ * launching anything: out[0] the ff_variant, out[1] rows and out[2] columns of the output tile a
+ * workgroup owns (small-M: all M rows x one 32-column strip at a time), out[3] wavefronts per
+ * workgroup, out[4] workgroups in the launch, out[5] tiles per workgroup (rounds), out[6] workgroups
+ * per compute unit, out[7] 1 if the tile order is the XCD-aware one.  `out` is host memory of eight
+ * ints.  Returns the status the call itself would return for a shape that cannot run.  With no GPU
+ * visible it plans for 256 compute units.
+ */
+int ff_plan_query(int64_t M, int64_t K, int64_t N, int dtype, int out[8]);
+
+/*
  * Bind caller-owned device memory (256-byte aligned) as the workspace of the
  * current device, or unbind with (NULL, 0), after which the library allocates
  * its own again.  The call clears the control region (the first MiB) of the

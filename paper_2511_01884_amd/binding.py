@@ -21,7 +21,7 @@ EXPORTS = [
     "ff_fused_linear_sub_rowmean_gelu_residual", "ff_rowmean_workspace_bytes",
     "ff_cross_entropy_mean", "ff_cross_entropy_workspace_bytes",
     "ff_metric_selection", "ff_metric_select_host",
-    "ff_workspace_bytes", "ff_set_workspace", "ff_check_device",
+    "ff_workspace_bytes", "ff_plan_query", "ff_set_workspace", "ff_check_device",
     "ff_status_string", "ff_version", "ff_last_variant", "ff_debug_linear",
     "ff_debug_force_variant", "ff_debug_force_tile", "ff_debug_force_waves", "ff_debug_set_stagger_us", "ff_debug_set_timeline", "ff_debug_copy", "ff_debug_mfma_loop", "ff_debug_stream_read", "ff_debug_set_wait_limit_us", "ff_debug_expect_extra_arrivals",
 ]
@@ -90,6 +90,8 @@ def load() -> ctypes.CDLL:
         lib.ff_debug_force_waves.argtypes = [ci]
         lib.ff_debug_set_stagger_us.restype = ci
         lib.ff_debug_set_stagger_us.argtypes = [ci]
+        lib.ff_plan_query.restype = ci
+        lib.ff_plan_query.argtypes = [i64, i64, i64, ci, ctypes.POINTER(ctypes.c_int)]
         lib.ff_debug_set_timeline.restype = ci
         lib.ff_debug_set_timeline.argtypes = [vp, ctypes.c_size_t]
         lib.ff_debug_set_wait_limit_us.restype = ci
@@ -134,6 +136,16 @@ def ff_version() -> int:
 
 def ff_last_variant() -> int:
     return int(load().ff_last_variant())
+
+
+def ff_plan_query(M: int, K: int, N: int, dtype: int) -> dict:
+    """The launch plan a call with this shape would take (no launch)."""
+    out = (ctypes.c_int * 8)()
+    rc = load().ff_plan_query(M, K, N, dtype, out)
+    if rc != FF_OK:
+        raise FFError(rc)
+    keys = ("variant", "tile_m", "tile_n", "waves", "grid", "rounds", "workgroups_per_cu", "xcd_order")
+    return dict(zip(keys, (int(v) for v in out)))
 
 
 def ff_workspace_bytes(M: int, K: int, N: int, dtype: int) -> int:

@@ -694,6 +694,32 @@ size_t ff_workspace_bytes(int64_t M, int64_t K, int64_t N, int dtype)
     return pl.total_bytes;
 }
 
+int ff_plan_query(int64_t M, int64_t K, int64_t N, int dtype, int out[8])
+{
+    if (out == nullptr)
+        return FF_ERR_NULL;
+    const int rc = validate_shape(M, K, N, dtype);
+    if (rc != FF_OK)
+        return rc;
+    std::lock_guard<std::mutex> lock(g_mutex);
+    DeviceState *st = current_device_state();
+    const int num_cus = st ? st->num_cus : 256;
+    Plan pl;
+    const int prc = make_plan(M, K, N, dtype, num_cus, st, g_forced_variant, false, pl);
+    if (prc != FF_OK)
+        return prc;
+    const bool small = pl.variant == FF_VARIANT_SMALL_M;
+    out[0] = pl.variant;
+    out[1] = small ? (int)M : pl.tile_m;
+    out[2] = small ? kSmallMStripCols : pl.tile_n;
+    out[3] = small ? 8 : tile_shape_waves(pl.shape);
+    out[4] = pl.grid;
+    out[5] = small ? 1 : pl.rounds;
+    out[6] = (pl.grid + num_cus - 1) / num_cus;
+    out[7] = (!small && pl.swz_sc_log2 >= 0) ? 1 : 0;
+    return FF_OK;
+}
+
 int ff_set_workspace(void *dev_ptr, size_t bytes)
 {
     std::lock_guard<std::mutex> lock(g_mutex);

@@ -739,26 +739,59 @@ void tile_kernel(const TileParams p)
             }
             __syncthreads();
             stamp(4);
-            if (tid < BM) {
-                // Plain loads: each line was written through by its single owner before
-                // the counter could reach its target, and no cache of this XCD can hold
-                // an older copy within this launch.  Loads are issued 16 at a time, the
-                // merge runs in tile order.
-                float na = 0.0f, mean_a = 0.0f, m2a = 0.0f;
-                for (int c0 = 0; c0 < p.NT; c0 += 16) {
+            // Plain loads: each line was written through by its single owner before the counter
+            // could reach its target, and no cache of this XCD can hold an older copy within this
+            // launch.  Loads are issued 16 at a time, the merge runs in tile order.  Where the
+            // workgroup has two threads per row and a row more than 16 tiles, each thread takes
+            // half of the row's tiles (the load latency, not the arithmetic, is what the merge
+            // costs) and the halves meet in LDS.
+            constexpr int kParts = (64 * kWaves >= 2 * BM) ? 2 : 1;
+            const bool split = kParts == 2 && p.NT > 16;
+            const int row = tid & (BM - 1);
+            const int per = split ? (p.NT + 1) / 2 : p.NT;
+            float na = 0.0f, mean_a = 0.0f, m2a = 0.0f;
+            if (tid < BM || (split && tid < kParts * BM)) {
+                // Buffer loads: a row block's partials as the resource, the tile as the scalar
+                // offset and the row as the one vector offset, so that no load needs a 64-bit
+                // address of its own in vector registers.
+                const int part = wave / (BM / 64);  // uniform in a wavefront
+                const __amdgpu_buffer_rsrc_t st_rsrc = __builtin_amdgcn_make_buffer_rsrc(
+                    reinterpret_cast<char *>(p.partials + (size_t)rb * p.NT * BM), 0,
+                    (unsigned)(p.NT * BM * (int)sizeof(floatx2)), 0x00020000);
+                const unsigned row_off = (unsigned)row * (unsigned)sizeof(floatx2);
+                const int c_begin = part * per < p.NT ? part * per : p.NT;
+                const int c_end = c_begin + per < p.NT ? c_begin + per : p.NT;
+                for (int c0 = c_begin; c0 < c_end; c0 += 16) {
                     floatx2 u[16];
 #pragma unroll
                     for (int j = 0; j < 16; ++j) {
-                        const int c = c0 + j < p.NT ? c0 + j : p.NT - 1;  // unconditional loads
-                        u[j] = p.partials[((size_t)rb * p.NT + c) * BM + tid];
+                        const int c = c0 + j < c_end ? c0 + j : c_end - 1;  // unconditional loads
+                        if (kParts == 2)
+                            u[j] = __builtin_bit_cast(floatx2, __builtin_amdgcn_raw_buffer_load_b64(
+                                                           st_rsrc, row_off, c * BM * (int)sizeof(floatx2), 0));
+                        else  // one thread per row: plain addressing takes fewer registers there
+                            u[j] = p.partials[((size_t)rb * p.NT + c) * BM + row];
                     }
 #pragma unroll
                     for (int j = 0; j < 16; ++j)
-                        if (c0 + j < p.NT) {
+                        if (c0 + j < c_end) {
                             const int c = c0 + j;
                             const int cnt = (N - c * BN < BN) ? (N - c * BN) : BN;
                             merge_stats(na, mean_a, m2a, (float)cnt, u[j][0], u[j][1]);
                         }
+                }
+                if (split && part == 1) {  // s_wst is free: its last readers passed the barriers above
+                    floatx2 o = {mean_a, m2a};
+                    s_wst[row] = o;
+                }
+            }
+            if (split)
+                __syncthreads();
+            if (tid < BM) {
+                if (split) {
+                    const int rest = N - per * BN;  // columns of the second half's tiles
+                    const floatx2 u = s_wst[row];
+                    merge_stats(na, mean_a, m2a, rest > 0 ? (float)rest : 0.0f, u[0], u[1]);
                 }
                 const float var = m2a / (float)N;
                 floatx2 o = {mean_a, 1.0f / sqrtf(var + p.eps)};

@@ -125,6 +125,7 @@ inline int tile_shape_rows(int shape)
 {
     return shape == kTile64 ? 64 : ((shape == kTile128 || shape == kTile256x128) ? 128 : 256);
 }
+inline int tile_shape_waves(int shape) { return shape == kTile256W8 ? 8 : 4; }
 hipError_t launch_tile_kernel(bool bf16, int shape, int mode, const TileParams &p, int grid, hipStream_t stream);
 int tile_kernel_blocks_per_cu(bool bf16, int shape, int mode);
 hipError_t launch_finalize_kernel(bool bf16, const FinalizeParams &p, hipStream_t stream);

@@ -13,7 +13,7 @@ import torch
 
 from .. import binding as B
 from .passes import PASSES
-from .variants import KERNEL_TAG, REPEATS, TASKS, VARIANTS
+from .variants import KERNEL_TAG, REPEATS, SECOND_PASS_TAG, SIZING_LAUNCHES, TASKS, VARIANTS
 
 LAUNCH_COLUMNS = ["LDS_Block_Size", "VGPR_Count", "Accum_VGPR_Count", "SGPR_Count", "Grid_Size_X"]
 
@@ -25,24 +25,32 @@ def _one(pattern):
     return found[0]
 
 
-def _variant_slices(dispatch_ids):
-    """Dispatches of the tagged kernel in launch order: one sizing launch, then REPEATS per variant;
-    the first launch of each variant is a warm-up."""
+def _variant_slices(dispatch_ids, variants=VARIANTS):
+    """Dispatches of one kernel in launch order: the sizing launches, then REPEATS per variant; the
+    first launch of each variant is a warm-up."""
     ids = sorted(dispatch_ids)
-    if len(ids) != 1 + REPEATS * len(VARIANTS):
-        raise RuntimeError("expected %d dispatches of %s, found %d" % (1 + REPEATS * len(VARIANTS), KERNEL_TAG, len(ids)))
-    ids = ids[1:]
-    return [ids[v * REPEATS + 1:(v + 1) * REPEATS] for v in range(len(VARIANTS))]
+    if len(ids) != SIZING_LAUNCHES + REPEATS * len(variants):
+        raise RuntimeError("expected %d dispatches, found %d" % (SIZING_LAUNCHES + REPEATS * len(variants), len(ids)))
+    ids = ids[SIZING_LAUNCHES:]
+    return [ids[v * REPEATS + 1:(v + 1) * REPEATS] for v in range(len(variants))]
+
+
+def _mean_us(by_id, ids):
+    return sum(int(by_id[i]["End_Timestamp"]) - int(by_id[i]["Start_Timestamp"]) for i in ids) / len(ids) / 1e3
 
 
 def read_task(task_dir):
-    """runtime_us[V], {metric: [V]} for one task."""
-    rows = [r for r in csv.DictReader(open(_one(os.path.join(task_dir, "trace", "**", "*kernel_trace.csv"))))
-            if KERNEL_TAG in r["Kernel_Name"]]
-    by_id = {int(r["Dispatch_Id"]): r for r in rows}
+    """runtime_us[V] of the tile kernel, runtime_us[V] of the second pass (0 for fused variants) and
+    {metric: [V]} for one task."""
+    trace = list(csv.DictReader(open(_one(os.path.join(task_dir, "trace", "**", "*kernel_trace.csv")))))
+    by_id = {int(r["Dispatch_Id"]): r for r in trace if KERNEL_TAG in r["Kernel_Name"]}
     slices = _variant_slices(by_id.keys())
-    runtime = [sum(int(by_id[i]["End_Timestamp"]) - int(by_id[i]["Start_Timestamp"]) for i in s) / len(s) / 1e3
-               for s in slices]
+    runtime = [_mean_us(by_id, s) for s in slices]
+    second = {int(r["Dispatch_Id"]): r for r in trace if SECOND_PASS_TAG in r["Kernel_Name"]}
+    two_pass = [v for v in VARIANTS if v[4] == B.FF_VARIANT_TILED_TWOPASS]
+    second_us = dict(zip((v[0] for v in two_pass),
+                         (_mean_us(second, s) for s in _variant_slices(second.keys(), two_pass))))
+    second_pass = [second_us.get(v[0], 0.0) for v in VARIANTS]
     metrics = {}
     for col in LAUNCH_COLUMNS:
         metrics["launch_" + col] = [sum(float(by_id[i][col]) for i in s) / len(s) for s in slices]
@@ -54,7 +62,18 @@ def read_task(task_dir):
         pslices = _variant_slices(acc.keys())
         for name in PASSES[p]:
             metrics[name] = [sum(acc[i][name] for i in s) / len(s) for s in pslices]
-    return runtime, metrics
+    return runtime, second_pass, metrics
+
+
+def _planned_variant(M, K, N):
+    """Label of the variant the automatic plan takes for a bf16 problem (ff_plan_query)."""
+    d = B.ff_plan_query(M, K, N, B.FF_BF16)
+    for v in VARIANTS:
+        if (d["tile_n"], d["tile_m"]) == ((256, 128) if (v[1], v[2]) == (256, 2) else (v[1], v[1])) and \
+                d["variant"] == v[4] and d["workgroups_per_cu"] == v[2] and \
+                (v[3] == 0 or d["waves"] == v[3]):
+            return v[0]
+    return None
 
 
 def main(argv) -> int:
@@ -62,10 +81,11 @@ def main(argv) -> int:
     tasks = [t for t in TASKS if os.path.isdir(os.path.join(out_dir, t))]
     if len(tasks) < 2:
         raise RuntimeError("need the dumps of at least two tasks under " + out_dir)
-    runtimes, tables = [], []
+    runtimes, seconds, tables = [], [], []
     for t in tasks:
-        rt, m = read_task(os.path.join(out_dir, t))
+        rt, sp, m = read_task(os.path.join(out_dir, t))
         runtimes.append(rt)
+        seconds.append(sp)
         tables.append(m)
     names = sorted(tables[0])
     values = torch.tensor([[[tab[nm][v] for nm in names] for v in range(len(VARIANTS))] for tab in tables],
@@ -85,6 +105,18 @@ def main(argv) -> int:
              "|---|" + "---|" * len(VARIANTS)]
     for t, rt in zip(tasks, runtimes):
         lines.append("| %s (%d x %d x %d) | " % ((t,) + TASKS[t]) + " | ".join("%.1f" % x for x in rt) + " |")
+    lines += ["", "## Runtime of the whole call per variant: tile kernel plus, for the two-pass variants, the",
+              "## normalisation kernel that follows it (microseconds; * marks the fastest of a task, P the",
+              "## automatic plan's choice)", "",
+              "| task (M x K x N) | " + " | ".join(v[0] for v in VARIANTS) + " |",
+              "|---|" + "---|" * len(VARIANTS)]
+    for t, rt, sp in zip(tasks, runtimes, seconds):
+        whole = [a + b for a, b in zip(rt, sp)]
+        M, K, N = TASKS[t]
+        planned = _planned_variant(M, K, N)
+        cells = ["%.1f%s%s" % (x, "*" if x == min(whole) else "", " P" if v[0] == planned else "")
+                 for x, v in zip(whole, VARIANTS)]
+        lines.append("| %s (%d x %d x %d) | " % (t, M, K, N) + " | ".join(cells) + " |")
     for title, tau in (("without the duplicate filter", 0.0), ("duplicates dropped at |r| >= 0.999", 0.999)):
         res = B.ff_metric_selection(values.cuda(), runtime.cuda(), top_k=20, percentile=75.0, collinear_tau=tau,
                                     min_tasks=2)

@@ -16,17 +16,22 @@ TASKS = {
     "mid": (8192, 2048, 8192),
     "flat": (1024, 4096, 8192),
 }
-# (label, tile, workgroups per compute unit, variant)
+# (label, tile, workgroups per compute unit, wavefronts per workgroup of the 256 x 256 tile or 0, variant)
 VARIANTS = [
-    ("t256_fused", 256, 1, B.FF_VARIANT_TILED_FUSED),
-    ("t256_twopass", 256, 1, B.FF_VARIANT_TILED_TWOPASS),
-    ("t128x1_fused", 128, 1, B.FF_VARIANT_TILED_FUSED),
-    ("t128x2_fused", 128, 2, B.FF_VARIANT_TILED_FUSED),
-    ("t128x1_twopass", 128, 1, B.FF_VARIANT_TILED_TWOPASS),
-    ("t128x2_twopass", 128, 2, B.FF_VARIANT_TILED_TWOPASS),
+    ("t256w8_fused", 256, 1, 8, B.FF_VARIANT_TILED_FUSED),
+    ("t256w8_twopass", 256, 1, 8, B.FF_VARIANT_TILED_TWOPASS),
+    ("t256w4_fused", 256, 1, 4, B.FF_VARIANT_TILED_FUSED),
+    ("t256w4_twopass", 256, 1, 4, B.FF_VARIANT_TILED_TWOPASS),
+    ("t256x128x2_fused", 256, 2, 0, B.FF_VARIANT_TILED_FUSED),
+    ("t128x1_fused", 128, 1, 0, B.FF_VARIANT_TILED_FUSED),
+    ("t128x2_fused", 128, 2, 0, B.FF_VARIANT_TILED_FUSED),
+    ("t128x1_twopass", 128, 1, 0, B.FF_VARIANT_TILED_TWOPASS),
+    ("t128x2_twopass", 128, 2, 0, B.FF_VARIANT_TILED_TWOPASS),
 ]
-REPEATS = 3          # launches per variant; the first is a warm-up and is not used
+REPEATS = 4          # launches per variant; the first is a warm-up and is not used
 KERNEL_TAG = "tile_kernel"
+SECOND_PASS_TAG = "finalize_kernel"   # one dispatch after every two-pass launch of the tile kernel
+SIZING_LAUNCHES = 40 # two-pass launches ahead of the variants: they size the workspace and load the chip
 
 
 def main(task: str) -> int:
@@ -42,14 +47,16 @@ def main(task: str) -> int:
     # size the workspace for the largest variant first so that no launch reallocates it
     B.ff_debug_force_variant(B.FF_VARIANT_TILED_TWOPASS)
     B.ff_debug_force_tile(128, 1)
-    B.ff_fused_linear_gelu_ln(X, W, b, gamma, beta, 1e-5, Y=Y)
+    for _ in range(SIZING_LAUNCHES):
+        B.ff_fused_linear_gelu_ln(X, W, b, gamma, beta, 1e-5, Y=Y)
     torch.cuda.synchronize()
     print("[variants] task %s: %d x %d x %d; dispatch order of %s:" % (task, M, K, N, KERNEL_TAG), flush=True)
-    print("[variants] 1 sizing launch, then %d launches each of: %s" %
-          (REPEATS, ", ".join(v[0] for v in VARIANTS)), flush=True)
+    print("[variants] %d sizing launches, then %d launches each of: %s" %
+          (SIZING_LAUNCHES, REPEATS, ", ".join(v[0] for v in VARIANTS)), flush=True)
     try:
-        for label, tile, per_cu, variant in VARIANTS:
+        for label, tile, per_cu, waves, variant in VARIANTS:
             B.ff_debug_force_tile(tile, per_cu)
+            B.ff_debug_force_waves(waves)
             B.ff_debug_force_variant(variant)
             for _ in range(REPEATS):
                 B.ff_fused_linear_gelu_ln(X, W, b, gamma, beta, 1e-5, Y=Y)
@@ -57,6 +64,7 @@ def main(task: str) -> int:
             B.ff_check_device()
     finally:
         B.ff_debug_force_tile(0, 0)
+        B.ff_debug_force_waves(0)
         B.ff_debug_force_variant(B.FF_VARIANT_AUTO)
     return 0
 

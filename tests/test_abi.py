@@ -85,3 +85,29 @@ def test_force_variant_rejects_unknown():
     assert lib.ff_debug_force_variant(0) == 0
     assert lib.ff_debug_set_wait_limit_us(0) == 2
     assert lib.ff_debug_set_wait_limit_us(2000000) == 0
+
+
+def test_plan_query_is_host_arithmetic():
+    """The automatic plan: one workgroup owns whole M for M <= 32 (bf16), else MFMA tiles whose size
+    follows from how many of them there are per compute unit (256 units assumed without a GPU)."""
+    q = lambda M, K, N, dt=B.FF_BF16: B.ff_plan_query(M, K, N, dt)
+    big = q(4096, 4096, 4096)
+    assert (big["variant"], big["tile_m"], big["tile_n"], big["waves"]) == (B.FF_VARIANT_TILED_FUSED, 256, 256, 8)
+    assert (big["grid"], big["rounds"], big["workgroups_per_cu"], big["xcd_order"]) == (256, 1, 1, 1)
+    assert q(65536, 1024, 1024)["rounds"] == 4 and q(8192, 4096, 16384)["rounds"] == 8
+    small = q(16, 8192, 8192)
+    assert small["variant"] == B.FF_VARIANT_SMALL_M and small["grid"] == 256
+    assert q(16, 8192, 8192, B.FF_F32)["variant"] == B.FF_VARIANT_TILED_FUSED   # the small-M kernel is bf16 only
+    assert q(33, 8192, 8192)["variant"] == B.FF_VARIANT_TILED_FUSED
+    flat = q(1024, 4096, 8192)      # 128 tiles of 256 x 256 would leave half the units idle
+    assert (flat["tile_m"], flat["grid"], flat["workgroups_per_cu"]) == (128, 512, 2)
+    tiny = q(256, 512, 512)
+    assert (tiny["tile_m"], tiny["grid"]) == (64, 32)
+    # a row of tiles wider than the launch cannot exchange statistics inside it: two passes
+    assert q(256, 512, 64 * 1024 * 2)["variant"] == B.FF_VARIANT_TILED_TWOPASS
+    with pytest.raises(B.FFError):
+        q(0, 8, 8)
+    with pytest.raises(B.FFError):
+        q(8, 12, 8)
+    lib = B.load()
+    assert lib.ff_plan_query(8, 8, 8, B.FF_BF16, None) == 1

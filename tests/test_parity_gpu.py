@@ -425,6 +425,32 @@ def test_two_workgroups_per_compute_unit_wait_for_each_other():
     assert torch.equal(Y, Y2)
 
 
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+@pytest.mark.parametrize("forced", [None, (256, 8), (256, 4)], ids=["auto", "t256w8", "t256w4"])
+def test_rows_of_more_than_sixteen_tiles(forced, dtype):
+    """Rows wider than 16 tiles: where a workgroup has two threads per row, each merges half of the row's
+    partial statistics.  Odd tile counts, a cut last tile (8 columns) and a cut last row block, with a
+    bias that moves the row mean far from zero."""
+    M, K, N = 700, 192, 5128       # 21 tiles of 256 columns, 41 of 128
+    _announce("wide rows %s" % (forced,), M, K, N)
+    d = make_inputs(M, K, N, dtype, seed=31)
+    d["b"] = (d["b"].float() + 3.0).to(d["b"].dtype)
+    try:
+        if forced:
+            B.ff_debug_force_tile(forced[0], 1)
+            B.ff_debug_force_waves(forced[1])
+        plan = B.ff_plan_query(M, K, N, B.FF_BF16 if dtype == "bf16" else B.FF_F32)
+        assert plan["variant"] == FUSED and -(-N // plan["tile_n"]) > 16
+        Y, used = gpu_run(d, AUTO)
+        Y2, _ = gpu_run(d, AUTO)
+    finally:
+        B.ff_debug_force_tile(0, 0)
+        B.ff_debug_force_waves(0)
+    assert used == FUSED
+    print(check_against_oracle(Y, oracle_on(d), dtype, "wide rows"))
+    assert torch.equal(Y, Y2)
+
+
 def test_workspace_grows_between_shapes():
     """Library-owned workspace: a larger shape after a smaller one reallocates and still works."""
     for (M, K, N) in ((64, 64, 64), (1500, 128, 3080), (300, 64, 520)):
