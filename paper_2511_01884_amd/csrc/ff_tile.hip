@@ -157,7 +157,17 @@ void tile_kernel(const TileParams p)
     constexpr int kEpiBytes = kOffOut + kWaves * 32 * kOutPitch;
     constexpr int kSmemBytes = (kSlabLdsBytes > kEpiBytes) ? kSlabLdsBytes : kEpiBytes;
 
-    __shared__ __attribute__((aligned(1024))) char smem[kSmemBytes];
+    // One LDS object for everything: with a second one the compiler can no longer tell the DMA's LDS
+    // writes from the fragment reads and waits for all loads in flight before every read.
+    constexpr int kPrmEarlyBytes = (PIPE != kPipeXReg) ? 3 * BN * 4 : 0;
+    __shared__ __attribute__((aligned(1024))) char smem[kSmemBytes + kPrmEarlyBytes];
+    // Bias, gamma and beta of the tile's columns.  With both operands travelling by DMA the three
+    // vectors are requested ahead of the first slab and parked in LDS of their own when it has
+    // landed, so that the epilogue finds them there; the register-staged pipeline, whose two
+    // workgroups per compute unit leave no LDS to spare, loads them when the K loop is over.
+    constexpr bool kPrmEarly = !kXReg;
+    constexpr int kPrmPerThread = (3 * BN + kThreads - 1) / kThreads;
+    float *s_prm_early = reinterpret_cast<float *>(smem + kSmemBytes);
 
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int wn = wave % kWavesN;
@@ -506,6 +516,20 @@ void tile_kernel(const TileParams p)
         // The previous tile's epilogue is done with the LDS once every wave is here (its LDS reads
         // completed before its stores could issue).  No wait for those stores: they drain while the
         // first slab of this tile travels.
+        // The parameter loads are the oldest loads in flight: every wait for a slab below covers them.
+        // Entry c of [bias | gamma | beta] goes to thread c % kThreads; loads never branch (what has
+        // no source reads the first element of W and is replaced by the default).
+        float prm[kPrmPerThread];
+#pragma unroll
+        for (int u = 0; u < kPrmPerThread; ++u) {
+            const int c = wave * 64 + lane + u * kThreads;
+            const int which = c / BN;
+            const int n = n0 + (c & (BN - 1));
+            const T *src = reinterpret_cast<const T *>(which == 0 ? p.b : (which == 1 ? p.gamma : p.beta));
+            const bool ok = which < 3 && n < N && src != nullptr;
+            const float v = load_as_float(ok ? src + n : reinterpret_cast<const T *>(p.W));
+            prm[u] = ok ? v : (which == 1 ? 1.0f : 0.0f);
+        }
         lds_barrier();
         dma_half_any(0, 0);
         dma_half_any(0, 1);
@@ -517,6 +541,13 @@ void tile_kernel(const TileParams p)
             __builtin_amdgcn_s_waitcnt(0x0f70);  // vmcnt(0): also the previous tile's stores, whose
                                                  // completion order relative to loads is not relied on
         first_tile = false;
+        // the previous tile's last readers of the parameter region passed the barrier above
+#pragma unroll
+        for (int u = 0; u < kPrmPerThread; ++u) {
+            const int c = wave * 64 + lane + u * kThreads;
+            if (c < 3 * BN)
+                s_prm_early[c] = prm[u];
+        }
         lds_barrier();
         stamp(1);
         stamp(kTimelineCycleSlot);
@@ -593,21 +624,23 @@ void tile_kernel(const TileParams p)
         const int M = opaque_uniform(p.M), N = opaque_uniform(p.N);
         const int h = lane >> 5;
         const int l32 = lane & 31;
-        float *s_b = reinterpret_cast<float *>(smem + kOffPrm);
+        float *s_b = kPrmEarly ? s_prm_early : reinterpret_cast<float *>(smem + kOffPrm);
         float *s_g = s_b + BN;
         float *s_be = s_g + BN;
         floatx2 *s_wst = reinterpret_cast<floatx2 *>(smem + kOffWst);
         floatx2 *s_rst = reinterpret_cast<floatx2 *>(smem + kOffRst);
         char *s_out = smem + kOffOut + wave * 32 * kOutPitch;
 
-        for (int c = wave * 64 + lane; c < BN; c += kThreads) {
-            const int n = n0 + c;
-            const bool ok = n < N;
-            s_b[c] = (ok && p.b) ? load_as_float(reinterpret_cast<const T *>(p.b) + n) : 0.0f;
-            s_g[c] = (ok && p.gamma) ? load_as_float(reinterpret_cast<const T *>(p.gamma) + n) : 1.0f;
-            s_be[c] = (ok && p.beta) ? load_as_float(reinterpret_cast<const T *>(p.beta) + n) : 0.0f;
+        if (!kPrmEarly) {
+            for (int c = wave * 64 + lane; c < BN; c += kThreads) {
+                const int n = n0 + c;
+                const bool ok = n < N;
+                s_b[c] = (ok && p.b) ? load_as_float(reinterpret_cast<const T *>(p.b) + n) : 0.0f;
+                s_g[c] = (ok && p.gamma) ? load_as_float(reinterpret_cast<const T *>(p.gamma) + n) : 1.0f;
+                s_be[c] = (ok && p.beta) ? load_as_float(reinterpret_cast<const T *>(p.beta) + n) : 0.0f;
+            }
+            __syncthreads();
         }
-        __syncthreads();
 
         const int ncol_wave = wn * WTN * 32;            // wave's first column inside the tile
         const int nvalid_tile = (N - n0 < BN) ? (N - n0) : BN;
