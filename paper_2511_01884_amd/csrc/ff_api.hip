@@ -136,20 +136,31 @@ int make_plan(int64_t M, int64_t K, int64_t N, int dtype, int num_cus, DeviceSta
         return FF_OK;
     }
 
-    // Tiled variants.  Large problems take 256 x 256 tiles, one workgroup of eight wavefronts per
-    // compute unit.  Eight wavefronts run the epilogue faster than four (two wavefronts per SIMD hide
-    // each other's latencies: bias, GELU and statistics 7.6 against 9.4 us per tile, stores 4.1 against
-    // 6.3 us) and the K loop up to 4 % slower (half again as many LDS fragment reads per MFMA); the
-    // sum favours eight (one device, us: 4096^3 115.7 against 116.7; 65536 x 1024 x 1024 159.5 against
-    // 170.7; 8192 x 4096 x 16384 950 against 966).  Problems of at most half the
-    // compute units' worth of 256-tiles take 128-tiles, two per compute unit, which finish in one
-    // round; at most a quarter of the compute units' worth of 128-tiles: 64-tiles, which spread them
-    // further.  The 256-column x 128-row tile, two workgroups per compute unit, is never chosen: the
-    // overlap of one workgroup's epilogue with the other's K loop does not pay for the 1.5 times larger
-    // L2 -> LDS traffic per flop (4096^3: 148 us).
+    // Tiled variants, by how many tiles of a shape there are per compute unit (measured on one device,
+    // 1024 x 4096 x 8192, whole call: 256 x 256 tiles 108 us with half the units idle, 256 x 128 tiles
+    // 82 us, 128 x 128 tiles two per unit 92 us, the same in two passes 84 us):
+    //   more 256 x 256 tiles than half the compute units: 256 x 256 tiles, one workgroup of eight
+    //     wavefronts per unit.  Eight wavefronts run the epilogue faster than four (two wavefronts per
+    //     SIMD hide each other's latencies) and the K loop up to 4 % slower (half again as many LDS
+    //     fragment reads per MFMA); the sum favours eight (4096^3 115.7 against 116.7 us; 65536 x 1024
+    //     x 1024 159.5 against 170.7; 8192 x 4096 x 16384 950 against 966);
+    //   else, in bf16, if the 128 x 128 tiles outnumber the units but the 256-column x 128-row tiles do
+    //     not: 256 x 128 tiles, one per unit, in one round (14 to 20 % faster than 128 x 128 tiles two
+    //     per unit on five such shapes; in fp32, where the K loop is eight times longer per slab and
+    //     that kernel spills, 128 x 128 tiles win by a third).  Two of those per unit are never chosen: the
+    //     overlap of one workgroup's epilogue with the other's K loop does not pay for the 1.5 times
+    //     larger L2 -> LDS traffic per flop (4096^3: 148 us);
+    //   else 128 x 128 tiles, up to two per unit, which finish in one round; and for at most a
+    //     quarter of the units' worth of those, 64 x 64 tiles, which spread them further.
     const int64_t tiles256 = ((M + 255) / 256) * ((N + 255) / 256);
+    const int64_t tiles256x128 = ((M + 127) / 128) * ((N + 255) / 256);
     const int64_t tiles128 = ((M + 127) / 128) * ((N + 127) / 128);
-    pl.shape = tiles256 * 2 > num_cus ? kTile256W8 : (tiles128 * 4 > num_cus ? kTile128 : kTile64);
+    if (tiles256 * 2 > num_cus)
+        pl.shape = kTile256W8;
+    else if (bf16 && tiles128 > num_cus && tiles256x128 <= num_cus)
+        pl.shape = kTile256x128;
+    else
+        pl.shape = tiles128 * 4 > num_cus ? kTile128 : kTile64;
     if (g_forced_tile != 0) {
         pl.shape = g_forced_tile == 64 ? kTile64 : (g_forced_tile == 128 ? kTile128 : kTile256);
         if (g_forced_tile == 256 && g_forced_wg_per_cu == 2)

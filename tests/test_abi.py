@@ -100,7 +100,11 @@ def test_plan_query_is_host_arithmetic():
     assert q(16, 8192, 8192, B.FF_F32)["variant"] == B.FF_VARIANT_TILED_FUSED   # the small-M kernel is bf16 only
     assert q(33, 8192, 8192)["variant"] == B.FF_VARIANT_TILED_FUSED
     flat = q(1024, 4096, 8192)      # 128 tiles of 256 x 256 would leave half the units idle
-    assert (flat["tile_m"], flat["grid"], flat["workgroups_per_cu"]) == (128, 512, 2)
+    assert (flat["tile_m"], flat["tile_n"], flat["grid"], flat["workgroups_per_cu"]) == (128, 256, 256, 1)
+    flat32 = q(1024, 4096, 8192, B.FF_F32)
+    assert (flat32["tile_m"], flat32["tile_n"], flat32["grid"], flat32["workgroups_per_cu"]) == (128, 128, 512, 2)
+    deep = q(2048, 8192, 2048)      # 256 tiles of 128 x 128: one per unit
+    assert (deep["tile_m"], deep["tile_n"], deep["grid"]) == (128, 128, 256)
     tiny = q(256, 512, 512)
     assert (tiny["tile_m"], tiny["grid"]) == (64, 32)
     # a row of tiles wider than the launch cannot exchange statistics inside it: two passes

@@ -413,14 +413,37 @@ def test_growing_the_own_workspace_during_capture_is_refused():
 
 
 def test_two_workgroups_per_compute_unit_wait_for_each_other():
-    """A shape for which the automatic plan takes 128-tiles with more workgroups than compute units
-    (two per unit, all of which must be resident because they wait for one another inside the launch)."""
+    """128-tiles with more workgroups than compute units (two per unit, all of which must be resident
+    because they wait for one another inside the launch)."""
     M, K, N = 1024, 256, 8192
     _announce("two per unit", M, K, N)
     d = make_inputs(M, K, N, "bf16", seed=26)
-    Y, used = gpu_run(d, AUTO)
+    try:
+        B.ff_debug_force_tile(128, 2)
+        plan = B.ff_plan_query(M, K, N, B.FF_BF16)
+        assert (plan["tile_m"], plan["tile_n"], plan["workgroups_per_cu"]) == (128, 128, 2)
+        Y, used = gpu_run(d, AUTO)
+        Y2, _ = gpu_run(d, AUTO)
+    finally:
+        B.ff_debug_force_tile(0, 0)
     assert used == FUSED
     print(check_against_oracle(Y, oracle_on(d), "bf16", "1024x256x8192"))
+    assert torch.equal(Y, Y2)
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_one_round_of_half_height_tiles(dtype):
+    """A shape whose 256 x 256 tiles would leave half the compute units idle: in bf16 the automatic plan
+    takes 256-column x 128-row tiles, one per unit.  Cut last tile column and row block."""
+    M, K, N = 1000, 320, 8136
+    _announce("half-height tiles", M, K, N)
+    plan = B.ff_plan_query(M, K, N, B.FF_BF16 if dtype == "bf16" else B.FF_F32)
+    want = (FUSED, 128, 256, 1) if dtype == "bf16" else (FUSED, 128, 128, 2)   # fp32 stays with 128 x 128 tiles
+    assert (plan["variant"], plan["tile_m"], plan["tile_n"], plan["workgroups_per_cu"]) == want
+    d = make_inputs(M, K, N, dtype, seed=33)
+    Y, used = gpu_run(d, AUTO)
+    assert used == FUSED
+    print(check_against_oracle(Y, oracle_on(d), dtype, "half-height tiles"))
     Y2, _ = gpu_run(d, AUTO)
     assert torch.equal(Y, Y2)
 
