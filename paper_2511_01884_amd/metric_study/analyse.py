@@ -66,13 +66,15 @@ def read_task(task_dir):
 
 
 def _planned_variant(M, K, N):
-    """Label of the variant the automatic plan takes for a bf16 problem (ff_plan_query)."""
+    """Label of the variant the automatic plan takes for a bf16 problem (ff_plan_query).  The 256 x 128
+    tile has one label whatever the number of workgroups per compute unit the grid comes to."""
     d = B.ff_plan_query(M, K, N, B.FF_BF16)
-    for v in VARIANTS:
-        if (d["tile_n"], d["tile_m"]) == ((256, 128) if (v[1], v[2]) == (256, 2) else (v[1], v[1])) and \
-                d["variant"] == v[4] and d["workgroups_per_cu"] == v[2] and \
-                (v[3] == 0 or d["waves"] == v[3]):
-            return v[0]
+    for label, tile, per_cu, waves, variant in VARIANTS:
+        half_height = (tile, per_cu) == (256, 2)
+        if d["variant"] != variant or (d["tile_n"], d["tile_m"]) != ((256, 128) if half_height else (tile, tile)):
+            continue
+        if half_height or (d["workgroups_per_cu"] == per_cu and (waves == 0 or d["waves"] == waves)):
+            return label
     return None
 
 

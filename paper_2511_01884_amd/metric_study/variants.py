@@ -16,13 +16,14 @@ TASKS = {
     "mid": (8192, 2048, 8192),
     "flat": (1024, 4096, 8192),
 }
-# (label, tile, workgroups per compute unit, wavefronts per workgroup of the 256 x 256 tile or 0, variant)
+# (label, tile, workgroups per compute unit, wavefronts per workgroup of the 256 x 256 tile or 0, variant);
+# tile 256 with two workgroups per unit is the 256-column x 128-row tile (one per unit where the grid is small)
 VARIANTS = [
     ("t256w8_fused", 256, 1, 8, B.FF_VARIANT_TILED_FUSED),
     ("t256w8_twopass", 256, 1, 8, B.FF_VARIANT_TILED_TWOPASS),
     ("t256w4_fused", 256, 1, 4, B.FF_VARIANT_TILED_FUSED),
     ("t256w4_twopass", 256, 1, 4, B.FF_VARIANT_TILED_TWOPASS),
-    ("t256x128x2_fused", 256, 2, 0, B.FF_VARIANT_TILED_FUSED),
+    ("t256x128_fused", 256, 2, 0, B.FF_VARIANT_TILED_FUSED),
     ("t128x1_fused", 128, 1, 0, B.FF_VARIANT_TILED_FUSED),
     ("t128x2_fused", 128, 2, 0, B.FF_VARIANT_TILED_FUSED),
     ("t128x1_twopass", 128, 1, 0, B.FF_VARIANT_TILED_TWOPASS),
