@@ -39,13 +39,13 @@ INFINITY_CACHE_BYTES = 256 << 20
 COMMON_SOURCES = ["ff_device.hpp"]   # device helpers every kernel includes
 TRAFFIC = {
     "cfg1": {"sources": ["ff_tile.hip"], "sha256": "8d1ac65f0bae9e49e6a6ab9f48ece2d86da6605b1c0a80955ecc583834cc654d",
-             "bytes": int((100500.0 * 2.0 + 33324.0 * 1.0) * 1024)},
+             "bytes": int((99551.0 * 2.0 + 33322.0 * 1.0) * 1024)},
     "cfg3": {"sources": ["ff_smallm.hip"], "sha256": "3d3b0c0d2dcbef9f914cc9f692bb843590916bdc620aa9ab6f9bbc9756d5264a",
-             "bytes": int((66916.0 * 2.0 + 339.0 * 1.0) * 1024)},
+             "bytes": int((66914.0 * 2.0 + 339.0 * 1.0) * 1024)},
     "xent": {"sources": ["ff_xent.hip"], "sha256": "6f6d24291f7ea6e33d3e4afae0ad2c30eade991481a459c8c95966b01b5506d1",
              "bytes": int((262700.0 * 2.0 + 32.1 * 1.0) * 1024)},
     "rowmean": {"sources": ["ff_rowmean.hip"], "sha256": "e5e79e742f35d38f9b13b80e0d38b9794bfaf330a93e1664410356d6bbd9ac6d",
-             "bytes": int((33204.0 * 2.0 + 32888.0 * 1.0) * 1024)},
+             "bytes": int((33203.0 * 2.0 + 32882.0 * 1.0) * 1024)},
 }
 
 
@@ -126,7 +126,7 @@ SMALLM_STAMPS = ["workgroup start", "first wavefront's K slice done", "all wavef
                  "other workgroups arrived", "statistics merged", "stores issued"]
 
 
-def phase_timeline(torch, B, step, small_m: bool, launches: int = 3):
+def phase_timeline(torch, B, step, small_m: bool, launches: int = 3, grid: int = 0):
     """Per-phase durations of one launch from the kernels' own timestamps (ff_debug_set_timeline): the mean,
     minimum and maximum over the workgroups' tiles of the last of `launches` launches."""
     slots, max_tiles = 16, 16 * 512
@@ -148,8 +148,18 @@ def phase_timeline(torch, B, step, small_m: bool, launches: int = 3):
     dur = rel[:, 1:] - rel[:, :-1]
     out = {"tiles": int(len(rec)), "last_stamp_us": float(rel[:, 6].max()), "phases": []}
     if not small_m:
-        mhz = (rec[:, 9] - rec[:, 8]) / ((rec[:, 2] - rec[:, 1]) / 100.0)
+        k_us = (rec[:, 2] - rec[:, 1]) / 100.0
+        mhz = (rec[:, 9] - rec[:, 8]) / k_us
         out["k_loop_shader_clock_mhz"] = float(mhz.mean())
+        if grid:
+            # workgroup w runs on XCD w % 8; records are stored at [round * grid + w]
+            live = (buf.cpu().view(-1, slots)[:, 0] > 0).nonzero().flatten()
+            xcd = (live % grid) % 8
+            out["k_loop_by_xcd"] = [{"xcd": x, "mean_us": float(k_us[xcd == x].mean()),
+                                     "spread_us": float(k_us[xcd == x].max() - k_us[xcd == x].min()),
+                                     "shader_clock_mhz": float(mhz[xcd == x].mean()),
+                                     "kilocycles": float((rec[:, 9] - rec[:, 8])[xcd == x].mean() / 1e3)}
+                                    for x in range(8) if bool((xcd == x).any())]
     for k in range(6):
         out["phases"].append({"from": names[k], "to": names[k + 1], "mean_us": float(dur[:, k].mean()),
                               "min_us": float(dur[:, k].min()), "max_us": float(dur[:, k].max())})
@@ -158,6 +168,9 @@ def phase_timeline(torch, B, step, small_m: bool, launches: int = 3):
     for ph in out["phases"]:
         print("  %-38s -> %-38s mean %6.1f  min %6.1f  max %6.1f us" %
               (ph["from"], ph["to"], ph["mean_us"], ph["min_us"], ph["max_us"]), file=sys.stderr)
+    for x in out.get("k_loop_by_xcd", []):
+        print("  K loop on XCD %d: mean %6.1f us (max - min %4.1f), shader clock %4.0f MHz, %5.1f thousand cycles" %
+              (x["xcd"], x["mean_us"], x["spread_us"], x["shader_clock_mhz"], x["kilocycles"]), file=sys.stderr)
     return out
 
 
@@ -260,7 +273,10 @@ def main() -> int:
 
     # the kernels' own phase timestamps, taken straight after the timed region: the sustained-ceiling
     # kernels further down leave the chip at a lower clock for a while
-    timeline = phase_timeline(torch, B, step, small_m=(variant == B.FF_VARIANT_SMALL_M)) if args.timeline else None
+    timeline = None
+    if args.timeline:
+        grid = B.ff_plan_query(M, K, N, B.FF_F32 if wl.dtype == "f32" else B.FF_BF16)["grid"]
+        timeline = phase_timeline(torch, B, step, small_m=(variant == B.FF_VARIANT_SMALL_M), grid=grid)
 
     hbm_bound = args.workload == "cfg3"
     if hbm_bound:
