@@ -1,6 +1,6 @@
 // Tiled MFMA path of the fused linear + erf-GELU + LayerNorm operator (gfx950).
 //
-// One workgroup (4 wavefronts) owns a BM x BN tile of the output and walks K in
+// One workgroup (4 or 8 wavefronts) owns a BM x BN tile of the output and walks K in
 // 128-byte slabs (whole cache lines: one L2 request per line).  X and W slabs go
 // HBM -> LDS with 16-byte direct-to-LDS loads into two stages; the loads of the
 // next slab are issued in the shadow of the MFMAs, the single barrier per slab
@@ -120,8 +120,10 @@ template <> struct MmaCount<float> { static constexpr int value = 4; };
 // slab by direct-to-LDS loads into two stages, the X slab through registers into a single buffer
 // (loaded a slab ahead, written between two barriers once everyone has read the previous one).
 // That fits a 256-column x 128-row tile into half the LDS (2 x 32 KB + 16 KB), so that two
-// workgroups share a compute unit: while one is in its epilogue (vector ALU, exchange, stores) the
-// other's K loop keeps the matrix pipe busy, and each covers the other's barrier stalls.
+// workgroups can share a compute unit: while one is in its epilogue (vector ALU, exchange, stores) the
+// other's K loop keeps the matrix pipe busy, and each covers the other's barrier stalls.  Measured, two
+// such workgroups per unit lose to one 256 x 256 tile (1.5 times the L2 -> LDS bytes per flop); the
+// shape earns its place one per unit, on problems whose 256 x 256 tiles would leave half the units idle.
 template <typename T, int kWavesN, int kWavesM, int WTN, int WTM, int MODE, bool RAGGED_N, int PIPE>
 __global__ __launch_bounds__(64 * kWavesN * kWavesM, (kWavesN * kWavesM * WTN * WTM <= 32) ? 2 : 1)
 void tile_kernel(const TileParams p)
