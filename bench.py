@@ -38,7 +38,7 @@ INFINITY_CACHE_BYTES = 256 << 20
 # their hash differs.
 COMMON_SOURCES = ["ff_device.hpp"]   # device helpers every kernel includes
 TRAFFIC = {
-    "cfg1": {"sources": ["ff_tile.hip"], "sha256": "8d1ac65f0bae9e49e6a6ab9f48ece2d86da6605b1c0a80955ecc583834cc654d",
+    "cfg1": {"sources": ["ff_tile.hip"], "sha256": "977a752d225258d91e2df06011e8c348b6938f706ae84c6743deef9000958301",
              "bytes": int((99551.0 * 2.0 + 33322.0 * 1.0) * 1024)},
     "cfg3": {"sources": ["ff_smallm.hip"], "sha256": "3d3b0c0d2dcbef9f914cc9f692bb843590916bdc620aa9ab6f9bbc9756d5264a",
              "bytes": int((66914.0 * 2.0 + 339.0 * 1.0) * 1024)},
