@@ -264,7 +264,8 @@ int ff_debug_stream_read(const void *src, size_t bytes);
 /* Tile shape of the tiled variants for later calls: tile = 0 (automatic), 64, 128 or 256 (columns);
  * wg_per_cu = 0 (automatic), 1 (a persistent grid of one workgroup per compute unit) or 2 (two).
  * (256, 0 or 1) is the 256 x 256 tile, one workgroup per compute unit; (256, 2) the 256-column x
- * 128-row tile, two per compute unit.  The shapes the automatic plan does not pick exist as distinct
+ * 128-row tile, up to two per compute unit (the automatic plan takes it only where there are no more
+ * such tiles than units).  The combinations the automatic plan does not pick exist as distinct
  * kernels of the same operator for the profiling-metric study and for tests.  FF_ERR_UNSUPPORTED
  * for any other combination. */
 int ff_debug_force_tile(int tile, int wg_per_cu);
