@@ -517,3 +517,37 @@ def test_eps_values(eps):
     d = dict(d, eps=eps)
     Y, _ = gpu_run(d, AUTO)
     print(check_against_oracle(Y, oracle_on(d), "f32", "eps %g" % eps))
+
+
+# ------------------------------------------------------------ seeded random shapes
+def _random_case(rng, large):
+    dtype = rng.choice(["bf16", "bf16", "f32"])
+    q = 8 if dtype == "bf16" else 4
+    if large:
+        M = rng.randint(900, 5000)
+        K = q * rng.randint(1, 384 // q)
+        N = q * rng.randint(2048 // q, 10000 // q)
+    else:
+        M = rng.choice([rng.randint(1, 40), rng.randint(1, 600), rng.randint(600, 2500)])
+        K = q * rng.randint(1, 768 // q)
+        N = q * rng.choice([rng.randint(1, 64), rng.randint(64, 1200), rng.randint(256, 6000 // q)])
+    return dtype, M, K, N
+
+
+@pytest.mark.parametrize("seed,large,cases", [(11, False, 24), (12, False, 24), (13, True, 10)])
+def test_random_shapes_against_the_oracle(seed, large, cases):
+    """Seeded random shapes through the automatic plan (every tile shape, the small-M kernel, cut tiles in
+    every dimension), a third of them with a bias that moves the row mean away from zero; full matrix
+    against the oracle, and a second run for bit equality."""
+    import random
+    rng = random.Random(seed)
+    for it in range(cases):
+        dtype, M, K, N = _random_case(rng, large)
+        d = make_inputs(M, K, N, dtype, seed=1000 * seed + it)
+        if rng.random() < 0.3:
+            d["b"] = (d["b"].float() + rng.choice([-2.0, 3.0])).to(d["b"].dtype)
+        _announce("random %d/%d" % (seed, it), M, K, N)
+        Y, _ = gpu_run(d, AUTO)
+        Y2, _ = gpu_run(d, AUTO)
+        check_against_oracle(Y, oracle_on(d), dtype, "random %dx%dx%d %s" % (M, K, N, dtype))
+        assert torch.equal(Y, Y2)
